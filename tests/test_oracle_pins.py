@@ -1,0 +1,436 @@
+"""Pins for the fp64 oracle: nothing here touches the GPU or the HIP library.
+
+Each test checks the oracle against something other than itself: a closed form,
+a library routine on a special case, an independently written brute force, or
+an invariant the paper states (merging per-shard partials reproduces attention
+over the whole K/V, Appendix B; pass-KV and pass-Q are exact, Section 3.5).
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rnd(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+# ---------------------------------------------------------------------------
+# independent brute force (pure Python loops over rows, tiny sizes only)
+# ---------------------------------------------------------------------------
+
+def brute_attn(q, k, v, q_pos, kv_pos, q_seq=None, kv_seq=None):
+    tq, nh, d = q.shape
+    nkv = k.shape[1]
+    out = np.zeros((tq, nh, d))
+    lse = np.full((tq, nh), -np.inf)
+    for i in range(tq):
+        for h in range(nh):
+            g = h // (nh // nkv)
+            num = np.zeros(d)
+            den = 0.0
+            for j in range(k.shape[0]):
+                if q_seq is not None and q_seq[i] != kv_seq[j]:
+                    continue
+                if kv_pos[j] <= q_pos[i]:
+                    w = math.exp(float(np.dot(q[i, h], k[j, g])) / math.sqrt(d))
+                    num += w * v[j, g]
+                    den += w
+            if den > 0:
+                out[i, h] = num / den
+                lse[i, h] = math.log(den)
+    return out, lse
+
+
+def test_attn_matches_brute_force_random_positions(oracle):
+    q, k, v = rnd(1, 23, 6, 8), rnd(2, 37, 3, 8), rnd(3, 37, 3, 8)
+    rng = np.random.default_rng(4)
+    q_pos = rng.integers(-1, 40, size=23)
+    q_pos[[2, 11]] = -1  # rows that see no key at all
+    kv_pos = rng.permutation(60)[:37]
+    o, l = oracle.attn(q, k, v, q_pos, kv_pos)
+    bo, bl = brute_attn(q, k, v, q_pos, kv_pos)
+    assert np.array_equal(np.isinf(l), np.isinf(bl))
+    fin = np.isfinite(bl)
+    assert fin.any() and (~fin).any()
+    np.testing.assert_allclose(o, bo, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(l[fin], bl[fin], rtol=0, atol=1e-12)
+    assert np.all(o[~fin] == 0)
+
+
+def test_attn_matches_brute_force_packed_batch(oracle):
+    cu_q = np.array([0, 3, 3, 9, 10])
+    cu_kv = np.array([0, 11, 15, 15, 30])
+    q, k, v = rnd(5, 10, 4, 4), rnd(6, 30, 1, 4), rnd(7, 30, 1, 4)
+    rng = np.random.default_rng(8)
+    q_pos, kv_pos = rng.integers(0, 20, size=10), rng.integers(0, 20, size=30)
+    q_seq = np.repeat(np.arange(4), np.diff(cu_q))
+    kv_seq = np.repeat(np.arange(4), np.diff(cu_kv))
+    o, l = oracle.attn(q, k, v, q_pos, kv_pos, cu_q=cu_q, cu_kv=cu_kv)
+    bo, bl = brute_attn(q, k, v, q_pos, kv_pos, q_seq, kv_seq)
+    assert np.array_equal(np.isinf(l), np.isinf(bl))
+    fin = np.isfinite(bl)
+    np.testing.assert_allclose(o, bo, atol=1e-12, rtol=0)
+    np.testing.assert_allclose(l[fin], bl[fin], atol=1e-12, rtol=0)
+    # sequence 2 (rows 3..8) has no keys at all
+    assert np.all(np.isinf(l[3:9]))
+
+
+# ---------------------------------------------------------------------------
+# library routine on the textbook special case (one rank, natural order)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("nh,nkv,d", [(4, 4, 16), (8, 2, 32), (16, 1, 64)])
+def test_unsharded_equals_torch_sdpa(oracle, nh, nkv, d):
+    t = 96
+    q, k, v = rnd(11, t, nh, d), rnd(12, t, nkv, d), rnd(13, t, nkv, d)
+    o, l = oracle.unsharded_causal(q, k, v)
+    tq = torch.from_numpy(q).permute(1, 0, 2)[None]
+    tk = torch.from_numpy(k).repeat_interleave(nh // nkv, dim=1).permute(1, 0, 2)[None]
+    tv = torch.from_numpy(v).repeat_interleave(nh // nkv, dim=1).permute(1, 0, 2)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+    ref = ref[0].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(o, ref, atol=1e-12, rtol=0)
+    # LSE through a different library path: logsumexp of the masked score matrix
+    s = torch.einsum("hid,hjd->hij", tq[0], tk[0]) / math.sqrt(d)
+    s = s.masked_fill(torch.ones(t, t, dtype=torch.bool).triu(1), float("-inf"))
+    np.testing.assert_allclose(l, torch.logsumexp(s, dim=-1).T.numpy(), atol=1e-12, rtol=0)
+
+
+# ---------------------------------------------------------------------------
+# closed forms
+# ---------------------------------------------------------------------------
+
+def test_first_token_sees_only_itself(oracle):
+    d = 32
+    q, k, v = rnd(21, 5, 2, d), rnd(22, 5, 1, d), rnd(23, 5, 1, d)
+    o, l = oracle.unsharded_causal(q, k, v)
+    for h in range(2):
+        np.testing.assert_allclose(o[0, h], v[0, 0], atol=1e-15)
+        assert abs(l[0, h] - np.dot(q[0, h], k[0, 0]) / math.sqrt(d)) < 1e-14
+
+
+def test_zero_keys_give_uniform_average_and_log_count(oracle):
+    # K == 0: every visible key scores 0, so LSE = ln(#visible), O = mean of visible V.
+    n, t = 4, 64
+    v = rnd(31, t, 1, 8)
+    q, k = rnd(32, t, 2, 8), np.zeros((t, 1, 8))
+    o, l = oracle.unsharded_causal(q, k, v)
+    cummean = np.cumsum(v[:, 0], axis=0) / np.arange(1, t + 1)[:, None]
+    for h in range(2):
+        np.testing.assert_allclose(l[:, h], np.log(np.arange(1, t + 1)), atol=1e-13)
+        np.testing.assert_allclose(o[:, h], cummean, atol=1e-13)
+    # per-partial counts for every (rank, shard) pair of the load-balanced layout
+    for r in range(n):
+        qp = oracle.shard_positions(t, n, r)
+        for s in range(n):
+            kp = oracle.shard_positions(t, n, s)
+            _, pl = oracle.attn(q[qp], k[kp], v[kp], qp, kp)
+            cnt = (kp[None, :] <= qp[:, None]).sum(axis=1)
+            expect = np.where(cnt > 0, np.log(np.maximum(cnt, 1)), -np.inf)
+            np.testing.assert_allclose(pl[:, 0], expect, atol=1e-13)
+
+
+def test_constant_values_pass_through(oracle):
+    t = 40
+    q, k = rnd(41, t, 4, 16), rnd(42, t, 2, 16)
+    c = rnd(43, 2, 16)
+    v = np.broadcast_to(c, (t, 2, 16)).copy()
+    qp = np.arange(t) - 3  # first three rows see nothing
+    o, l = oracle.attn(q, k, v, qp, np.arange(t))
+    assert np.all(np.isinf(l[:3])) and np.all(o[:3] == 0)
+    for h in range(4):
+        np.testing.assert_allclose(o[3:, h], np.broadcast_to(c[h // 2], (t - 3, 16)), atol=1e-14)
+
+
+def test_softmax_scale_is_inverse_sqrt_head_dim(oracle):
+    # one query, two keys with q.k = a and b: LSE = log(e^{a/sqrt d} + e^{b/sqrt d})
+    d = 64
+    q = np.zeros((1, 1, d)); q[0, 0, 0] = 2.0
+    k = np.zeros((2, 1, d)); k[0, 0, 0] = 3.0; k[1, 0, 0] = -1.0
+    v = np.zeros((2, 1, d)); v[0, 0, 1] = 1.0; v[1, 0, 2] = 1.0
+    o, l = oracle.attn(q, k, v, [5], [0, 1])
+    a, b = 6.0 / 8.0, -2.0 / 8.0
+    assert abs(l[0, 0] - math.log(math.exp(a) + math.exp(b))) < 1e-15
+    assert abs(o[0, 0, 1] - math.exp(a) / (math.exp(a) + math.exp(b))) < 1e-15
+    assert abs(o[0, 0, 2] - math.exp(b) / (math.exp(a) + math.exp(b))) < 1e-15
+    # explicit scale overrides the default
+    _, l2 = oracle.attn(q, k, v, [5], [0, 1], scale=1.0)
+    assert abs(l2[0, 0] - math.log(math.exp(6.0) + math.exp(-2.0))) < 1e-14
+
+
+def test_gqa_head_grouping_is_contiguous(oracle):
+    # With V_g = g * ones, query head h must return h // group.
+    t, nh, nkv, d = 6, 6, 3, 4
+    q, k = rnd(51, t, nh, d), rnd(52, t, nkv, d)
+    v = np.zeros((t, nkv, d))
+    for g in range(nkv):
+        v[:, g] = g
+    o, _ = oracle.unsharded_causal(q, k, v)
+    for h in range(nh):
+        np.testing.assert_allclose(o[:, h], h // 2, atol=1e-14)
+
+
+def test_joint_permutation_of_keys_changes_nothing(oracle):
+    q, k, v = rnd(61, 17, 4, 8), rnd(62, 29, 2, 8), rnd(63, 29, 2, 8)
+    q_pos = np.random.default_rng(64).integers(0, 29, size=17)
+    kv_pos = np.arange(29)
+    o, l = oracle.attn(q, k, v, q_pos, kv_pos)
+    perm = np.random.default_rng(65).permutation(29)
+    o2, l2 = oracle.attn(q, k[perm], v[perm], q_pos, kv_pos[perm])
+    np.testing.assert_allclose(o2, o, atol=1e-13)
+    np.testing.assert_allclose(l2, l, atol=1e-13)
+
+
+def test_inclusive_diagonal(oracle):
+    # a key at exactly the query's position is visible, one position later is not
+    q, k, v = rnd(71, 1, 1, 4), rnd(72, 2, 1, 4), rnd(73, 2, 1, 4)
+    o, _ = oracle.attn(q, k, v, [7], [7, 8])
+    np.testing.assert_allclose(o[0, 0], v[0, 0], atol=1e-15)
+
+
+# ---------------------------------------------------------------------------
+# merge (Equation 4)
+# ---------------------------------------------------------------------------
+
+def test_merge_equal_lse_is_arithmetic_mean(oracle):
+    a, b = rnd(81, 5, 3, 8), rnd(82, 5, 3, 8)
+    l = rnd(83, 5, 3)
+    o, ml = oracle.merge([a, b], [l, l])
+    np.testing.assert_allclose(o, 0.5 * (a + b), atol=1e-15)
+    np.testing.assert_allclose(ml, l + math.log(2.0), atol=1e-14)
+
+
+def test_merge_with_empty_partial_is_identity(oracle):
+    a, l = rnd(84, 7, 2, 4), rnd(85, 7, 2)
+    junk = np.full_like(a, np.nan)  # an empty partial's O must not be read into the result
+    o, ml = oracle.merge([a, junk], [l, np.full_like(l, -np.inf)])
+    np.testing.assert_array_equal(o, a)
+    np.testing.assert_array_equal(ml, l)
+
+
+def test_merge_all_empty_is_zero_and_minus_inf(oracle):
+    a = rnd(86, 3, 2, 4)
+    ninf = np.full((3, 2), -np.inf)
+    o, ml = oracle.merge([a, a, a], [ninf, ninf, ninf])
+    assert np.all(o == 0) and np.all(np.isneginf(ml))
+
+
+def test_merge_two_point_closed_form(oracle):
+    # weights are the softmax of the LSEs: w0 = 1/(1+e^{l1-l0})
+    a, b = np.array([[1.0, 0.0]]), np.array([[0.0, 1.0]])
+    o, ml = oracle.merge([a, b], [np.array([math.log(3.0)]), np.array([math.log(1.0)])])
+    np.testing.assert_allclose(o, [[0.75, 0.25]], atol=1e-15)
+    assert abs(ml[0] - math.log(4.0)) < 1e-15
+
+
+def test_merge_is_associative_with_merged_lse(oracle):
+    outs = [rnd(90 + i, 6, 2, 4) for i in range(4)]
+    lses = [rnd(95 + i, 6, 2) * 3 for i in range(4)]
+    lses[1][0, 0] = -np.inf
+    o_all, l_all = oracle.merge(outs, lses)
+    o01, l01 = oracle.merge(outs[:2], lses[:2])
+    o23, l23 = oracle.merge(outs[2:], lses[2:])
+    o2, l2 = oracle.merge([o01, o23], [l01, l23])
+    np.testing.assert_allclose(o2, o_all, atol=1e-14)
+    np.testing.assert_allclose(l2, l_all, atol=1e-14)
+
+
+def test_merge_of_disjoint_key_sets_equals_attention_on_union(oracle):
+    # Appendix B's claim, checked against the independent brute force
+    q, k, v = rnd(101, 9, 4, 8), rnd(102, 31, 2, 8), rnd(103, 31, 2, 8)
+    q_pos = np.random.default_rng(104).integers(0, 31, size=9)
+    kv_pos = np.arange(31)
+    parts = [np.arange(0, 31, 3), np.arange(1, 31, 3), np.arange(2, 31, 3)]
+    po, pl = zip(*[oracle.attn(q, k[p], v[p], q_pos, kv_pos[p]) for p in parts])
+    o, l = oracle.merge(po, pl)
+    bo, bl = brute_attn(q, k, v, q_pos, kv_pos)
+    np.testing.assert_allclose(o, bo, atol=1e-13)
+    np.testing.assert_allclose(l, bl, atol=1e-13)
+
+
+# ---------------------------------------------------------------------------
+# sharding (Section 3.5.1)
+# ---------------------------------------------------------------------------
+
+def _read_golden_sharding():
+    cases = []
+    with open(os.path.join(GOLDEN, "load_balanced_sharding.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            head, chunks = line.split(":")
+            n, rank = [int(x) for x in head.split()]
+            cases.append((n, rank, [int(x) for x in chunks.split()]))
+    return cases
+
+
+def test_sharding_matches_paper_chunk_assignment(oracle):
+    chunk = 5
+    for n, rank, chunks in _read_golden_sharding():
+        pos = oracle.shard_positions(2 * n * chunk, n, rank)
+        expect = np.concatenate([np.arange(c * chunk, (c + 1) * chunk) for c in chunks])
+        np.testing.assert_array_equal(pos, expect)
+
+
+@pytest.mark.parametrize("t,n", [(512, 2), (37, 3), (5, 4), (1, 2), (0, 2), (64, 1), (1000, 16)])
+def test_every_position_owned_exactly_once(oracle, t, n):
+    allpos = np.concatenate([oracle.shard_positions(t, n, r) for r in range(n)])
+    np.testing.assert_array_equal(np.sort(allpos), np.arange(t))
+    sizes = [len(oracle.shard_positions(t, n, r)) for r in range(n)]
+    assert max(sizes) <= 2 * (-(-t // (2 * n))) if t else max(sizes) == 0
+
+
+def test_tiny_config_ranges(oracle):
+    # 512 tokens, 2 ranks, 4 chunks of 128: rank 0 holds chunks 0 and 3, rank 1 chunks 1 and 2
+    r0 = oracle.shard_positions(512, 2, 0)
+    r1 = oracle.shard_positions(512, 2, 1)
+    np.testing.assert_array_equal(r0, np.r_[0:128, 384:512])
+    np.testing.assert_array_equal(r1, np.r_[128:384])
+
+
+@pytest.mark.parametrize("n,chunk", [(2, 128), (4, 8), (16, 3)])
+def test_load_balance_closed_form(oracle, n, chunk):
+    # With 2N chunks of S tokens every rank sees 2N*S^2 + S (query, key) pairs in total,
+    # 2S^2 against every other rank's shard and 2S^2 + S against its own.
+    t = 2 * n * chunk
+    q, k, v = rnd(111, t, 1, 2), rnd(112, t, 1, 2), rnd(113, t, 1, 2)
+    for r in range(n):
+        qp = oracle.shard_positions(t, n, r)
+        total = 0
+        for s in range(n):
+            kp = oracle.shard_positions(t, n, s)
+            _, _, pairs = oracle.attn(q[qp], k[kp], v[kp], qp, kp, return_pairs=True)
+            assert pairs == 2 * chunk * chunk + (chunk if s == r else 0)
+            total += pairs
+        assert total == 2 * n * chunk * chunk + chunk
+
+
+def test_closed_form_pair_counts_at_benchmark_sizes():
+    # the same closed form at the sizes the benchmark uses (no attention run)
+    assert 2 * 2 * 128 ** 2 + 128 == 65664
+    assert 2 * 16 * 4096 ** 2 + 4096 == 536875008
+    assert 2 * 16 * 32768 ** 2 + 32768 == 34359771136
+
+
+# ---------------------------------------------------------------------------
+# the invariant: ring + merge == unsharded causal attention
+# ---------------------------------------------------------------------------
+
+def _shard_full_prefill(oracle, q, k, v, n):
+    t = q.shape[0]
+    pos = [oracle.shard_positions(t, n, r) for r in range(n)]
+    return ([q[p] for p in pos], [k[p] for p in pos], [v[p] for p in pos], list(pos), list(pos))
+
+
+@pytest.mark.parametrize("n,t", [(1, 33), (2, 64), (3, 50), (4, 61), (16, 97), (4, 5)])
+def test_ring_passkv_and_passq_reproduce_unsharded(oracle, n, t):
+    q, k, v = rnd(121, t, 4, 8), rnd(122, t, 2, 8), rnd(123, t, 2, 8)
+    ref_o, ref_l = oracle.unsharded_causal(q, k, v)
+    qs, ks, vs, qp, kp = _shard_full_prefill(oracle, q, k, v, n)
+    o_kv, l_kv, _, _ = oracle.ring_passkv(qs, ks, vs, qp, kp)
+    o_q, l_q, _, _ = oracle.ring_passq(qs, ks, vs, qp, kp)
+    for r in range(n):
+        np.testing.assert_allclose(o_kv[r], ref_o[qp[r]], atol=1e-12)
+        np.testing.assert_allclose(l_kv[r], ref_l[qp[r]], atol=1e-12)
+        np.testing.assert_allclose(o_q[r], o_kv[r], atol=1e-13)
+        np.testing.assert_allclose(l_q[r], l_kv[r], atol=1e-13)
+
+
+def test_ring_passkv_with_padded_equal_size_messages(oracle):
+    # Algorithm 2 pads every rank's KV to the same length; pads carry a position no
+    # query can reach, and padded query rows carry position -1 and see nothing.
+    n, t = 3, 20
+    q, k, v = rnd(131, t, 2, 4), rnd(132, t, 1, 4), rnd(133, t, 1, 4)
+    ref_o, ref_l = oracle.unsharded_causal(q, k, v)
+    qs, ks, vs, qp, kp = _shard_full_prefill(oracle, q, k, v, n)
+    lmax = max(len(p) for p in kp)
+    big = np.iinfo(np.int32).max
+    for r in range(n):
+        pad = lmax - len(kp[r]) + 2
+        junk = np.full((pad,) + k.shape[1:], 1e3)
+        ks[r] = np.concatenate([ks[r], junk]); vs[r] = np.concatenate([vs[r], junk])
+        kp[r] = np.concatenate([kp[r], np.full(pad, big)]).astype(np.int32)
+        qs[r] = np.concatenate([qs[r], np.full((1,) + q.shape[1:], 7.0)])
+        qp[r] = np.concatenate([qp[r], [-1]]).astype(np.int32)
+    o, l, _, _ = oracle.ring_passkv(qs, ks, vs, qp, kp)
+    for r in range(n):
+        np.testing.assert_allclose(o[r][:-1], ref_o[qp[r][:-1]], atol=1e-12)
+        np.testing.assert_allclose(l[r][:-1], ref_l[qp[r][:-1]], atol=1e-12)
+        assert np.all(o[r][-1] == 0) and np.all(np.isneginf(l[r][-1]))
+
+
+@pytest.mark.parametrize("partition", ["balanced", "contiguous"])
+@pytest.mark.parametrize("n,p,t", [(2, 40, 8), (4, 37, 11), (3, 0, 13)])
+def test_partial_prefill_is_independent_of_cache_partition(oracle, partition, n, p, t):
+    q = rnd(141, t, 4, 8)
+    k, v = rnd(142, p + t, 1, 8), rnd(143, p + t, 1, 8)
+    ref_o, ref_l = oracle.unsharded_causal(q, k, v, p_cached=p)
+    sh = oracle.shard_partial_prefill(p, t, n, cache_partition=partition)
+    qs = [q[qp - p] for qp, _ in sh]
+    ks = [k[kp] for _, kp in sh]
+    vs = [v[kp] for _, kp in sh]
+    qp = [a for a, _ in sh]
+    kp = [b for _, b in sh]
+    for drv in (oracle.ring_passq, oracle.ring_passkv):
+        o, l, _, _ = drv(qs, ks, vs, qp, kp)
+        for r in range(n):
+            np.testing.assert_allclose(o[r], ref_o[qp[r] - p], atol=1e-12)
+            np.testing.assert_allclose(l[r], ref_l[qp[r] - p], atol=1e-12)
+
+
+@pytest.mark.parametrize("decode_iter", [0, 1, 5])
+def test_batched_decode_is_independent_of_owner_rank(oracle, decode_iter):
+    n, nh, d = 4, 4, 8
+    lengths = [9, 1, 30, 17, 2, 12]
+    ks = [rnd(150 + b, L, 1, d) for b, L in enumerate(lengths)]
+    vs = [rnd(160 + b, L, 1, d) for b, L in enumerate(lengths)]
+    qs = [rnd(170 + b, 1, nh, d) for b in range(len(lengths))]
+    ref = [oracle.attn(qs[b], ks[b], vs[b], [L - 1], np.arange(L))
+           for b, L in enumerate(lengths)]
+    ranks = oracle.shard_decode_batch(lengths, n, decode_iter)
+    rk, rv, rq = [], [], []
+    for r in ranks:
+        rk.append(np.concatenate([ks[b][p][None] for b, p in zip(r["kv_seq"], r["kv_pos"])])
+                  if len(r["kv_pos"]) else np.zeros((0, 1, d)))
+        rv.append(np.concatenate([vs[b][p][None] for b, p in zip(r["kv_seq"], r["kv_pos"])])
+                  if len(r["kv_pos"]) else np.zeros((0, 1, d)))
+        rq.append(np.concatenate([qs[b] for b in r["bid"]]) if len(r["bid"])
+                  else np.zeros((0, nh, d)))
+    o, l, _, _ = oracle.ring_passq_decode(rq, [r["bid"] for r in ranks],
+                                          [r["q_pos"] for r in ranks], rk, rv,
+                                          [r["kv_pos"] for r in ranks],
+                                          [r["cu_kv"] for r in ranks])
+    seen = set()
+    for s, r in enumerate(ranks):
+        for i, b in enumerate(r["bid"]):
+            assert (b + decode_iter) % n == s
+            np.testing.assert_allclose(o[s][i], ref[b][0][0], atol=1e-12)
+            np.testing.assert_allclose(l[s][i], ref[b][1][0], atol=1e-12)
+            seen.add(int(b))
+    assert seen == set(range(len(lengths)))
+
+
+# ---------------------------------------------------------------------------
+# planted mistakes: each plausible slip in a re-implementation must trip a pin above
+# ---------------------------------------------------------------------------
+
+def test_pins_detect_planted_mistakes(oracle):
+    t, d = 12, 4
+    q, k, v = rnd(181, t, 2, d), rnd(182, t, 1, d), rnd(183, t, 1, d)
+    good_o, good_l = oracle.unsharded_causal(q, k, v)
+    pos = np.arange(t)
+    # exclusive diagonal
+    o, l = oracle.attn(q, k, v, pos - 1, pos)
+    assert np.isneginf(l[0]).all() and not np.allclose(o[1:], good_o[1:])
+    # missing scale
+    _, l = oracle.attn(q, k, v, pos, pos, scale=1.0)
+    assert not np.allclose(l[1:], good_l[1:])
+    # transposed mask (key sees query)
+    o, _ = oracle.attn(q, k, v, -pos, -pos)
+    assert not np.allclose(o, good_o)
