@@ -1,0 +1,240 @@
+/*
+ * cp_attn.h - C ABI of the per-rank hot path of context-parallel ring attention
+ * on one MI355X (gfx950).
+ *
+ * The library computes, for one context-parallel (CP) rank, exact GQA attention
+ * of a query shard against one KV shard under a position-based causal mask,
+ * returning a partial output and its log-sum-exp, and the LSE-weighted merge of
+ * such partials. Drivers iterate N virtual CP ranks on the one GPU in the order
+ * of the paper's ring algorithms. No communication is performed.
+ *
+ * Conventions for every entry point
+ *   - Tensors are token-major, as in Section 3.4:
+ *       Q   [tokens, n_q_heads,  head_dim]
+ *       K,V [tokens, n_kv_heads, head_dim]
+ *       O   [tokens, n_q_heads,  head_dim]
+ *       LSE [tokens, n_q_heads]            (always fp32, natural log)
+ *     densely packed, 16-byte aligned. Query head h reads KV head
+ *     h / (n_q_heads / n_kv_heads).
+ *   - Pointers marked (device) are HIP device pointers owned by the caller; the
+ *     library never allocates, frees or retains device memory and keeps no
+ *     state between calls. Pointers marked (host) are read during the call only.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream) and the call returns without synchronising.
+ *   - The return value is CP_OK (0) or a negative cp_status. Arguments are
+ *     checked on the host before anything is launched; on error nothing is
+ *     enqueued. No exception or abort crosses this boundary.
+ *   - Outputs are fully overwritten. A query row that sees no key gets O = 0
+ *     and LSE = -inf.
+ *   - Key j is visible to query i iff kv_pos[j] <= q_pos[i] (and, for packed
+ *     batches, both belong to the same sequence). Padding is expressed through
+ *     positions: a padded KV slot carries CP_POS_PAD_KV, a padded query row
+ *     carries CP_POS_PAD_Q.
+ */
+#ifndef CP_ATTN_H
+#define CP_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CP_POS_PAD_KV INT32_MAX /* never visible to any query */
+#define CP_POS_PAD_Q (-1)       /* sees no key */
+
+typedef enum {
+  CP_OK = 0,
+  CP_ERR_NULL = -1,        /* a required pointer is NULL */
+  CP_ERR_SHAPE = -2,       /* negative or inconsistent sizes, head ratio, batch */
+  CP_ERR_UNSUPPORTED = -3, /* dtype / head_dim / combination not implemented */
+  CP_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned or too small */
+  CP_ERR_LAUNCH = -5,      /* HIP reported a launch failure */
+  CP_ERR_ALIGN = -6        /* a tensor pointer is not 16-byte aligned */
+} cp_status;
+
+typedef enum { CP_BF16 = 0, CP_FP32 = 1 } cp_dtype;
+
+/* Which computation a workspace is sized for (cp_workspace_bytes). */
+typedef enum {
+  CP_WS_PARTIAL = 0, /* cp_attn_partial  */
+  CP_WS_DECODE = 1,  /* cp_attn_decode   */
+  CP_WS_MERGE = 2    /* cp_attn_merge (needs none; returns 0) */
+} cp_ws_kind;
+
+/* Problem shape of one attention call. */
+typedef struct {
+  int32_t dtype;      /* cp_dtype of Q, K, V */
+  int32_t head_dim;   /* 64 or 128 */
+  int32_t n_q_heads;  /* N_H  on this GPU */
+  int32_t n_kv_heads; /* N_KV on this GPU; divides n_q_heads */
+  int32_t batch;      /* number of packed sequences; 1 when cu_seqlens are NULL */
+  int32_t reserved;   /* must be 0 */
+  int64_t total_q;    /* packed query tokens  (>= 0) */
+  int64_t total_kv;   /* packed KV tokens     (>= 0) */
+  float softmax_scale; /* <= 0 selects 1/sqrt(head_dim) (Appendix B) */
+  float reserved_f;    /* must be 0 */
+} cp_shape;
+
+/*
+ * Load-balanced sharding (Section 3.5.1): a sequence of `total` tokens is cut
+ * into 2N chunks of ceil(total/2N) tokens (trailing chunks short or empty) and
+ * rank i owns chunk i followed by chunk 2N-1-i. Writes the owned positions,
+ * each plus `offset`, to pos_out (host, may be NULL to query the count only)
+ * and the count to *n_out (host). Host-only; touches no device.
+ * The count never exceeds 2*ceil(total/2N).
+ */
+int cp_shard_positions(int64_t total, int64_t offset, int32_t n_ranks, int32_t rank,
+                       int32_t* pos_out, int64_t* n_out);
+
+/*
+ * Bytes of device workspace a call of the given kind needs for this shape
+ * (an upper bound valid for any positions). 0 if none. Returns 0 for an
+ * invalid shape (the call itself will report the error).
+ */
+size_t cp_workspace_bytes(const cp_shape* shape, int32_t kind);
+
+/*
+ * Partial attention of one ring step: O, LSE = Attn(Q, KV) as used in
+ * Algorithm 2 ("Compute O_k^s <- GQA(Q_k, KV^s_k)") and Algorithm 3, with O and
+ * LSE as defined in Appendix B, over the keys visible under the causal rule of
+ * Section 3.5.1.
+ *
+ *   shape         (host)
+ *   q, k, v       (device) dtype shape->dtype
+ *   q_pos         (device) int32 [total_q]   absolute positions
+ *   kv_pos        (device) int32 [total_kv]
+ *   cu_seqlens_q  (device) int32 [batch+1] packed sequence starts, or NULL iff batch == 1
+ *   cu_seqlens_kv (device) int32 [batch+1], NULL iff cu_seqlens_q is NULL
+ *   out           (device) [total_q, n_q_heads, head_dim] of out_dtype (cp_dtype)
+ *   lse           (device) fp32 [total_q, n_q_heads]
+ *   workspace     (device) >= cp_workspace_bytes(shape, CP_WS_PARTIAL), 256-byte
+ *                 aligned; may be NULL when that size is 0
+ *
+ * bf16 inputs with head_dim 128 run on the MFMA kernel (fully masked KV tiles
+ * are skipped; short query shards are split over the KV axis through the
+ * workspace). Other combinations run on an fp32 vector kernel.
+ */
+int cp_attn_partial(const cp_shape* shape, const void* q, const void* k, const void* v,
+                    const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_q,
+                    const int32_t* cu_seqlens_kv, void* out, float* lse, int32_t out_dtype,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Decode attention of one pass-Q ring step: Algorithm 4,
+ * "O_s^k <- GQA(Q^s_k, KV_k[bid^s_k])". Each of the shape->total_q query tokens
+ * (one per travelling sequence) attends to the KV segment of its own sequence
+ * inside this rank's packed KV.
+ *
+ *   shape->batch   number of sequences packed in k, v (size of cu_seqlens_kv - 1)
+ *   shape->total_q number of query tokens in this call (may be < batch)
+ *   bid    (device) int32 [total_q] sequence id of each query, in [0, batch)
+ *   q_pos  (device) int32 [total_q]
+ *   kv_pos (device) int32 [total_kv]
+ *   cu_seqlens_kv (device) int32 [batch+1]
+ *   workspace: cp_workspace_bytes(shape, CP_WS_DECODE) bytes, 256-byte aligned.
+ *
+ * The KV axis of every sequence is split across workgroups and the split
+ * results are combined with the merge rule of Equation 4 before returning
+ * (split-KV decode). Requires bf16 and head_dim 128, n_q_heads/n_kv_heads <= 16.
+ */
+int cp_attn_decode(const cp_shape* shape, const void* q, const void* k, const void* v,
+                   const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_kv,
+                   const int32_t* bid, void* out, float* lse, int32_t out_dtype,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Merge attention, Appendix B Equation 4:
+ *   O = sum_s O^s exp(LSE^s - LSE^max) / sum_s exp(LSE^s - LSE^max),
+ * and LSE = LSE^max + log sum_s exp(LSE^s - LSE^max). Rows whose partials are
+ * all empty (LSE = -inf) give O = 0, LSE = -inf; the O of an empty partial is
+ * never read into the result.
+ *
+ *   rows      number of (token, head) rows = tokens * n_q_heads
+ *   head_dim  multiple of 8, <= 256
+ *   outs      (host) array of n_parts (device) pointers, each [rows, head_dim] of part_dtype
+ *   lses      (host) array of n_parts (device) pointers, each fp32 [rows]
+ *   out       (device) [rows, head_dim] of out_dtype
+ *   lse_out   (device) fp32 [rows], or NULL
+ *   1 <= n_parts <= CP_MAX_PARTS
+ */
+#define CP_MAX_PARTS 64
+int cp_attn_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* const* outs,
+                  const float* const* lses, int32_t part_dtype, void* out, int32_t out_dtype,
+                  float* lse_out, void* stream);
+
+/*
+ * Descriptor of a ring over n_ranks virtual CP ranks that all live on this GPU.
+ * Per-rank arrays are (host) arrays of length n_ranks.
+ */
+typedef struct {
+  int32_t dtype, head_dim, n_q_heads, n_kv_heads;
+  float softmax_scale; /* <= 0 selects 1/sqrt(head_dim) */
+  int32_t n_ranks;
+  int32_t out_dtype;   /* dtype of the merged outputs */
+  int32_t part_dtype;  /* dtype of the partial outputs: CP_FP32 or CP_BF16 */
+  const int64_t* n_q;  /* (host) query tokens of rank k */
+  const int64_t* n_kv; /* (host) KV tokens of rank k */
+  const void* const* q;         /* (host) -> (device) Q_k  [n_q[k], n_q_heads, head_dim] */
+  const void* const* k;         /* (host) -> (device) K_k  [n_kv[k], n_kv_heads, head_dim] */
+  const void* const* v;         /* (host) -> (device) V_k */
+  const int32_t* const* q_pos;  /* (host) -> (device) int32 [n_q[k]] */
+  const int32_t* const* kv_pos; /* (host) -> (device) int32 [n_kv[k]] */
+  void* const* out;             /* (host) -> (device) merged O_k of out_dtype */
+  float* const* lse;            /* (host) -> (device) merged LSE_k, entries or array may be NULL */
+  /*
+   * Partial-result buffers (device). Slot i holds max_n_q * n_q_heads * head_dim
+   * elements of part_dtype in partial_out and max_n_q * n_q_heads floats in
+   * partial_lse, where max_n_q = max_k n_q[k]. With keep_partials == 0 there are
+   * n_ranks slots, reused for every rank (slot s = KV origin rank in pass-KV,
+   * = KV holder rank in pass-Q). With keep_partials != 0 there are
+   * n_ranks * n_ranks slots and the partial of queries of rank a against KV of
+   * rank b stays in slot a * n_ranks + b.
+   */
+  void* partial_out;
+  float* partial_lse;
+  int32_t keep_partials;
+  int32_t reserved;
+  void* workspace; /* (device) max over ranks of the per-call workspace */
+  size_t workspace_bytes;
+  /* decode only (cp_ring_passq_decode); NULL otherwise */
+  int32_t batch;                       /* sequences packed in every rank's KV */
+  const int32_t* const* cu_seqlens_kv; /* (host) -> (device) int32 [batch+1] per rank */
+  const int32_t* const* bid;           /* (host) -> (device) int32 [n_q[k]] per rank */
+} cp_ring_desc;
+
+/*
+ * Ring pass-KV, Algorithm 2, for every virtual rank k: for j = 0..N-1,
+ * s = (k - j) mod N, O_k^s = GQA(Q_k, KV^s); then O_k = merge_s(O_k^s)
+ * (Equation 4). The SendRecv of the algorithm is elided: KV^s is read in place.
+ */
+int cp_ring_passkv(const cp_ring_desc* desc, void* stream);
+
+/*
+ * Ring pass-Q prefill, Algorithm 3: rank k computes O_s^k = GQA(Q^s, KV_k) for
+ * s = (k - j) mod N; the permute + All2All that returns partials to their
+ * source rank is the choice of output slot; then O_s = merge_k(O_s^k).
+ */
+int cp_ring_passq(const cp_ring_desc* desc, void* stream);
+
+/*
+ * Batched ring pass-Q decode, Algorithm 4: as cp_ring_passq with one query token
+ * per sequence, batch ids travelling with the queries, and KV_k[bid] lookups
+ * through cu_seqlens_kv[k]. Uses cp_attn_decode for every step.
+ */
+int cp_ring_passq_decode(const cp_ring_desc* desc, void* stream);
+
+/* Workspace the ring drivers need: the maximum over all (query rank, KV rank) calls. */
+size_t cp_ring_workspace_bytes(const cp_ring_desc* desc, int32_t decode);
+
+/* Static description of a cp_status. Never NULL. */
+const char* cp_strerror(int status);
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int cp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CP_ATTN_H */

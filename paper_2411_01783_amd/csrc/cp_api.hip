@@ -1,0 +1,339 @@
+// C-ABI entry points: host-side argument checks, kernel selection, ring drivers.
+#include <math.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "cp_common.h"
+
+using namespace cp;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+int check_shape(const cp_shape* s) {
+  if (s == nullptr) return CP_ERR_NULL;
+  if (s->dtype != CP_BF16 && s->dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
+  if (s->head_dim != 64 && s->head_dim != 128) return CP_ERR_UNSUPPORTED;
+  if (s->n_q_heads < 1 || s->n_kv_heads < 1 || s->n_q_heads % s->n_kv_heads != 0)
+    return CP_ERR_SHAPE;
+  if (s->batch < 1 || s->total_q < 0 || s->total_kv < 0) return CP_ERR_SHAPE;
+  if (s->total_q > 0x7fffffffLL || s->total_kv > 0x7fffffffLL) return CP_ERR_SHAPE;
+  if (s->reserved != 0 || s->reserved_f != 0.f) return CP_ERR_SHAPE;
+  if (!(s->softmax_scale == s->softmax_scale) || isinf(s->softmax_scale)) return CP_ERR_SHAPE;
+  return CP_OK;
+}
+
+inline float resolve_scale(float scale, int head_dim) {
+  return scale > 0.f ? scale : 1.0f / sqrtf((float)head_dim);
+}
+
+inline bool mfma_prefill_applies(const cp_shape& s) {
+  return s.dtype == CP_BF16 && s.head_dim == 128 && s.batch == 1 &&
+         (s.n_q_heads / s.n_kv_heads) <= 64;
+}
+
+inline size_t elem_size(int32_t dtype) { return dtype == CP_FP32 ? 4 : 2; }
+
+}  // namespace
+
+extern "C" {
+
+int cp_version(void) { return 100; }
+
+const char* cp_strerror(int status) {
+  switch (status) {
+    case CP_OK: return "ok";
+    case CP_ERR_NULL: return "a required pointer is NULL";
+    case CP_ERR_SHAPE: return "invalid or inconsistent shape";
+    case CP_ERR_UNSUPPORTED: return "dtype / head_dim / combination not supported";
+    case CP_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case CP_ERR_LAUNCH: return "HIP kernel launch failed";
+    case CP_ERR_ALIGN: return "tensor pointer is not 16-byte aligned";
+    default: return "unknown status";
+  }
+}
+
+int cp_shard_positions(int64_t total, int64_t offset, int32_t n_ranks, int32_t rank,
+                       int32_t* pos_out, int64_t* n_out) {
+  if (n_out == nullptr) return CP_ERR_NULL;
+  if (total < 0 || n_ranks < 1 || rank < 0 || rank >= n_ranks) return CP_ERR_SHAPE;
+  if (offset < 0 || total + offset > 0x7fffffffLL) return CP_ERR_SHAPE;
+  const int64_t n_chunks = 2 * (int64_t)n_ranks;
+  const int64_t size = (total + n_chunks - 1) / n_chunks;
+  const int64_t chunk[2] = {rank, n_chunks - 1 - rank};
+  int64_t n = 0;
+  for (int c = 0; c < 2; ++c) {
+    const int64_t lo = std::min(chunk[c] * size, total);
+    const int64_t hi = std::min((chunk[c] + 1) * size, total);
+    for (int64_t p = lo; p < hi; ++p, ++n)
+      if (pos_out != nullptr) pos_out[n] = (int32_t)(p + offset);
+  }
+  *n_out = n;
+  return CP_OK;
+}
+
+size_t cp_workspace_bytes(const cp_shape* shape, int32_t kind) {
+  if (check_shape(shape) != CP_OK) return 0;
+  switch (kind) {
+    case CP_WS_PARTIAL:
+      return mfma_prefill_applies(*shape) ? prefill_mfma_workspace_bytes(*shape) : 0;
+    case CP_WS_DECODE:
+      return decode_workspace_bytes(*shape);
+    default:
+      return 0;
+  }
+}
+
+int cp_attn_partial(const cp_shape* shape, const void* q, const void* k, const void* v,
+                    const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_q,
+                    const int32_t* cu_seqlens_kv, void* out, float* lse, int32_t out_dtype,
+                    void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != CP_OK) return rc;
+  const cp_shape& s = *shape;
+  if (out_dtype != CP_BF16 && out_dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
+  if ((cu_seqlens_q == nullptr) != (cu_seqlens_kv == nullptr)) return CP_ERR_NULL;
+  if (cu_seqlens_q == nullptr && s.batch != 1) return CP_ERR_SHAPE;
+  if (s.total_q > 0 && (q == nullptr || q_pos == nullptr || out == nullptr || lse == nullptr))
+    return CP_ERR_NULL;
+  if (s.total_q > 0 && s.total_kv > 0 && (k == nullptr || v == nullptr || kv_pos == nullptr))
+    return CP_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return CP_ERR_ALIGN;
+  if (s.total_q == 0) return CP_OK;
+  const float scale = resolve_scale(s.softmax_scale, s.head_dim);
+  hipStream_t st = (hipStream_t)stream;
+  if (mfma_prefill_applies(s) && cu_seqlens_q == nullptr) {
+    const size_t need = prefill_mfma_workspace_bytes(s);
+    if (need > 0 && (workspace == nullptr || !aligned256(workspace) || workspace_bytes < need))
+      return CP_ERR_WORKSPACE;
+    return launch_prefill_mfma(s, scale, q, k, v, q_pos, kv_pos, out, lse, out_dtype, workspace,
+                               workspace_bytes, st);
+  }
+  return launch_partial_generic(s, scale, q, k, v, q_pos, kv_pos, cu_seqlens_q, cu_seqlens_kv,
+                                out, lse, out_dtype, st);
+}
+
+int cp_attn_decode(const cp_shape* shape, const void* q, const void* k, const void* v,
+                   const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_kv,
+                   const int32_t* bid, void* out, float* lse, int32_t out_dtype,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != CP_OK) return rc;
+  const cp_shape& s = *shape;
+  if (out_dtype != CP_BF16 && out_dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
+  if (s.dtype != CP_BF16 || s.head_dim != 128) return CP_ERR_UNSUPPORTED;
+  if (s.n_q_heads / s.n_kv_heads > 16) return CP_ERR_UNSUPPORTED;
+  if (cu_seqlens_kv == nullptr) return CP_ERR_NULL;
+  if (s.total_q > 0 &&
+      (q == nullptr || q_pos == nullptr || bid == nullptr || out == nullptr || lse == nullptr))
+    return CP_ERR_NULL;
+  if (s.total_q > 0 && s.total_kv > 0 && (k == nullptr || v == nullptr || kv_pos == nullptr))
+    return CP_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return CP_ERR_ALIGN;
+  if (s.total_q == 0) return CP_OK;
+  const size_t need = decode_workspace_bytes(s);
+  if (need > 0 && (workspace == nullptr || !aligned256(workspace) || workspace_bytes < need))
+    return CP_ERR_WORKSPACE;
+  const float scale = resolve_scale(s.softmax_scale, s.head_dim);
+  return launch_decode(s, scale, q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid, out, lse, out_dtype,
+                       workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int cp_attn_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* const* outs,
+                  const float* const* lses, int32_t part_dtype, void* out, int32_t out_dtype,
+                  float* lse_out, void* stream) {
+  if (rows < 0 || head_dim < 8 || head_dim > 256 || head_dim % 8 != 0) return CP_ERR_SHAPE;
+  if (n_parts < 1 || n_parts > CP_MAX_PARTS) return CP_ERR_SHAPE;
+  if ((part_dtype != CP_BF16 && part_dtype != CP_FP32) ||
+      (out_dtype != CP_BF16 && out_dtype != CP_FP32))
+    return CP_ERR_UNSUPPORTED;
+  if (outs == nullptr || lses == nullptr) return CP_ERR_NULL;
+  if (rows > 0) {
+    if (out == nullptr) return CP_ERR_NULL;
+    for (int s = 0; s < n_parts; ++s) {
+      if (outs[s] == nullptr || lses[s] == nullptr) return CP_ERR_NULL;
+      if (!aligned16(outs[s])) return CP_ERR_ALIGN;
+    }
+    if (!aligned16(out)) return CP_ERR_ALIGN;
+  }
+  if (rows == 0) return CP_OK;
+  return launch_merge(rows, head_dim, n_parts, outs, lses, part_dtype, out, out_dtype, lse_out,
+                      (hipStream_t)stream);
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------
+// ring drivers
+// ---------------------------------------------------------------------------
+
+static int check_ring(const cp_ring_desc* d, bool decode) {
+  if (d == nullptr) return CP_ERR_NULL;
+  if (d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS) return CP_ERR_SHAPE;
+  if (d->reserved != 0) return CP_ERR_SHAPE;
+  if (d->n_q == nullptr || d->n_kv == nullptr || d->q == nullptr || d->k == nullptr ||
+      d->v == nullptr || d->q_pos == nullptr || d->kv_pos == nullptr || d->out == nullptr)
+    return CP_ERR_NULL;
+  if (d->partial_out == nullptr || d->partial_lse == nullptr) return CP_ERR_NULL;
+  if (d->part_dtype != CP_BF16 && d->part_dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
+  if (d->out_dtype != CP_BF16 && d->out_dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
+  if (!aligned16(d->partial_out)) return CP_ERR_ALIGN;
+  if (decode) {
+    if (d->batch < 1 || d->cu_seqlens_kv == nullptr || d->bid == nullptr) return CP_ERR_NULL;
+  }
+  cp_shape s = {};
+  s.dtype = d->dtype; s.head_dim = d->head_dim; s.n_q_heads = d->n_q_heads;
+  s.n_kv_heads = d->n_kv_heads; s.batch = decode ? d->batch : 1;
+  s.softmax_scale = d->softmax_scale;
+  int rc = check_shape(&s);
+  if (rc != CP_OK) return rc;
+  for (int r = 0; r < d->n_ranks; ++r) {
+    if (d->n_q[r] < 0 || d->n_kv[r] < 0) return CP_ERR_SHAPE;
+    if (d->n_q[r] > 0 && (d->q[r] == nullptr || d->q_pos[r] == nullptr || d->out[r] == nullptr))
+      return CP_ERR_NULL;
+    if (d->n_kv[r] > 0 && (d->k[r] == nullptr || d->v[r] == nullptr || d->kv_pos[r] == nullptr))
+      return CP_ERR_NULL;
+    if (decode && (d->cu_seqlens_kv[r] == nullptr || (d->n_q[r] > 0 && d->bid[r] == nullptr)))
+      return CP_ERR_NULL;
+  }
+  return CP_OK;
+}
+
+static cp_shape ring_shape(const cp_ring_desc* d, int q_rank, int kv_rank, bool decode) {
+  cp_shape s = {};
+  s.dtype = d->dtype; s.head_dim = d->head_dim; s.n_q_heads = d->n_q_heads;
+  s.n_kv_heads = d->n_kv_heads; s.batch = decode ? d->batch : 1;
+  s.total_q = d->n_q[q_rank]; s.total_kv = d->n_kv[kv_rank];
+  s.softmax_scale = d->softmax_scale;
+  return s;
+}
+
+extern "C" size_t cp_ring_workspace_bytes(const cp_ring_desc* d, int32_t decode) {
+  if (check_ring(d, decode != 0) != CP_OK) return 0;
+  size_t need = 0;
+  for (int a = 0; a < d->n_ranks; ++a)
+    for (int b = 0; b < d->n_ranks; ++b) {
+      cp_shape s = ring_shape(d, a, b, decode != 0);
+      need = std::max(need, cp_workspace_bytes(&s, decode ? CP_WS_DECODE : CP_WS_PARTIAL));
+    }
+  return need;
+}
+
+namespace {
+
+struct RingSlots {
+  int64_t max_q = 0;
+  size_t out_slot_bytes = 0;
+  size_t lse_slot_elems = 0;
+  char* out_base = nullptr;
+  float* lse_base = nullptr;
+  void* out(int64_t slot) const { return out_base + slot * out_slot_bytes; }
+  float* lse(int64_t slot) const { return lse_base + slot * lse_slot_elems; }
+};
+
+RingSlots make_slots(const cp_ring_desc* d) {
+  RingSlots r;
+  for (int i = 0; i < d->n_ranks; ++i) r.max_q = std::max<int64_t>(r.max_q, d->n_q[i]);
+  r.lse_slot_elems = (size_t)r.max_q * d->n_q_heads;
+  r.out_slot_bytes = r.lse_slot_elems * d->head_dim * elem_size(d->part_dtype);
+  r.out_base = (char*)d->partial_out;
+  r.lse_base = d->partial_lse;
+  return r;
+}
+
+// One partial-attention call of the ring: queries of rank `a` against KV of rank `b`.
+int ring_partial(const cp_ring_desc* d, bool decode, int a, int b, void* o, float* l,
+                 hipStream_t st) {
+  cp_shape s = ring_shape(d, a, b, decode);
+  if (decode)
+    return cp_attn_decode(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b],
+                          d->cu_seqlens_kv[b], d->bid[a], o, l, d->part_dtype, d->workspace,
+                          d->workspace_bytes, st);
+  return cp_attn_partial(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b], nullptr,
+                         nullptr, o, l, d->part_dtype, d->workspace, d->workspace_bytes, st);
+}
+
+int ring_merge(const cp_ring_desc* d, const RingSlots& slots, int a, int64_t first_slot,
+               hipStream_t st) {
+  const void* outs[CP_MAX_PARTS];
+  const float* lses[CP_MAX_PARTS];
+  for (int s = 0; s < d->n_ranks; ++s) {
+    outs[s] = slots.out(first_slot + s);
+    lses[s] = slots.lse(first_slot + s);
+  }
+  float* lse_out = d->lse != nullptr ? d->lse[a] : nullptr;
+  return cp_attn_merge(d->n_q[a] * d->n_q_heads, d->head_dim, d->n_ranks, outs, lses,
+                       d->part_dtype, d->out[a], d->out_dtype, lse_out, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
+  int rc = check_ring(d, false);
+  if (rc != CP_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const RingSlots slots = make_slots(d);
+  const int n = d->n_ranks;
+  // Algorithm 2 as seen from each rank k in turn: N ring steps, then a local merge.
+  for (int k = 0; k < n; ++k) {
+    const int64_t base = d->keep_partials ? (int64_t)k * n : 0;
+    for (int j = 0; j < n; ++j) {
+      const int s = ((k - j) % n + n) % n;  // origin rank of the KV held at step j
+      rc = ring_partial(d, false, k, s, slots.out(base + s), slots.lse(base + s), st);
+      if (rc != CP_OK) return rc;
+    }
+    rc = ring_merge(d, slots, k, base, st);
+    if (rc != CP_OK) return rc;
+  }
+  return CP_OK;
+}
+
+static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
+  int rc = check_ring(d, decode);
+  if (rc != CP_OK) return rc;
+  hipStream_t st = (hipStream_t)stream;
+  const RingSlots slots = make_slots(d);
+  const int n = d->n_ranks;
+  if (d->keep_partials) {
+    // Algorithms 3 / 4 in ring order: at step j rank k holds the queries of rank
+    // s = (k - j) mod N. Writing the result to slot [s][k] is the permute + All2All.
+    for (int j = 0; j < n; ++j)
+      for (int k = 0; k < n; ++k) {
+        const int s = ((k - j) % n + n) % n;
+        rc = ring_partial(d, decode, s, k, slots.out((int64_t)s * n + k),
+                          slots.lse((int64_t)s * n + k), st);
+        if (rc != CP_OK) return rc;
+      }
+    for (int s = 0; s < n; ++s) {
+      rc = ring_merge(d, slots, s, (int64_t)s * n, st);
+      if (rc != CP_OK) return rc;
+    }
+    return CP_OK;
+  }
+  // With N reusable slots the same N*N calls are issued grouped by source rank s
+  // (for each s the holders k = s, s+1, ... in ring order), so that the N partials of
+  // one source are complete, and can be merged, before the slots are reused.
+  for (int s = 0; s < n; ++s) {
+    for (int j = 0; j < n; ++j) {
+      const int k = (s + j) % n;
+      rc = ring_partial(d, decode, s, k, slots.out(k), slots.lse(k), st);
+      if (rc != CP_OK) return rc;
+    }
+    rc = ring_merge(d, slots, s, 0, st);
+    if (rc != CP_OK) return rc;
+  }
+  return CP_OK;
+}
+
+int cp_ring_passq(const cp_ring_desc* d, void* stream) { return ring_passq_common(d, false, stream); }
+
+int cp_ring_passq_decode(const cp_ring_desc* d, void* stream) {
+  return ring_passq_common(d, true, stream);
+}
+
+}  // extern "C"

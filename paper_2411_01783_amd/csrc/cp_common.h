@@ -1,0 +1,72 @@
+// Internal declarations shared by the HIP translation units of libcp_attn.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "cp_attn.h"
+
+namespace cp {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float to_float(float x) { return x; }
+__device__ __forceinline__ float to_float(bf16_t x) { return static_cast<float>(x); }
+
+template <typename T>
+__device__ __forceinline__ T from_float(float x);
+template <>
+__device__ __forceinline__ float from_float<float>(float x) {
+  return x;
+}
+template <>
+__device__ __forceinline__ bf16_t from_float<bf16_t>(float x) {
+  return static_cast<bf16_t>(x);
+}
+
+// ---- launchers (each returns a cp_status; enqueue on `stream` only) ----
+
+// fp32 vector kernel: any supported dtype / head_dim, packed batches.
+int launch_partial_generic(const cp_shape& s, float scale, const void* q, const void* k,
+                           const void* v, const int32_t* q_pos, const int32_t* kv_pos,
+                           const int32_t* cu_q, const int32_t* cu_kv, void* out, float* lse,
+                           int32_t out_dtype, hipStream_t stream);
+
+// bf16 MFMA kernel, head_dim 128, batch 1.
+size_t prefill_mfma_workspace_bytes(const cp_shape& s);
+int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
+                        const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
+                        float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
+                        hipStream_t stream);
+
+// split-KV decode, bf16, head_dim 128.
+size_t decode_workspace_bytes(const cp_shape& s);
+int launch_decode(const cp_shape& s, float scale, const void* q, const void* k, const void* v,
+                  const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_kv,
+                  const int32_t* bid, void* out, float* lse, int32_t out_dtype, void* workspace,
+                  size_t workspace_bytes, hipStream_t stream);
+
+// Equation 4 over n_parts partials given as device pointers.
+int launch_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* const* outs,
+                 const float* const* lses, int32_t part_dtype, void* out, int32_t out_dtype,
+                 float* lse_out, hipStream_t stream);
+
+// Equation 4 over n_parts partials laid out with a constant stride (split-KV scratch).
+int launch_merge_strided(int64_t rows, int32_t head_dim, int32_t n_parts, const float* parts_out,
+                         const float* parts_lse, int64_t part_stride_rows, void* out,
+                         int32_t out_dtype, float* lse_out, hipStream_t stream);
+
+inline int check_launch() {
+  return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
+}
+
+}  // namespace cp

@@ -1,0 +1,176 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, validates arguments before touching a device, and its sharding
+function agrees with the oracle's."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2411_01783_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2411_01783_amd import build
+        build.build()
+    return B.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "cp_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(cp_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_strerror(lib):
+    assert B.cp_version() >= 100
+    assert B.strerror(0) == "ok"
+    for code in range(-6, 0):
+        assert B.strerror(code) not in ("ok", "unknown status")
+    assert B.strerror(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("total,n", [(512, 2), (131072, 16), (37, 3), (5, 4), (1, 2), (0, 2),
+                                     (64, 1), (1000, 16), (4095, 16)])
+def test_shard_positions_matches_oracle(lib, oracle, total, n):
+    for rank in range(n):
+        for offset in (0, 131072):
+            got = B.cp_shard_positions(total, n, rank, offset)
+            want = oracle.shard_positions(total, n, rank, offset)
+            np.testing.assert_array_equal(got, want)
+
+
+def test_shard_positions_rejects_bad_arguments(lib):
+    n = ctypes.c_int64(0)
+    f = lib.cp_shard_positions
+    assert f(10, 0, 2, 0, None, None) == -1
+    assert f(-1, 0, 2, 0, None, ctypes.byref(n)) == -2
+    assert f(10, 0, 0, 0, None, ctypes.byref(n)) == -2
+    assert f(10, 0, 2, 2, None, ctypes.byref(n)) == -2
+    assert f(10, -1, 2, 0, None, ctypes.byref(n)) == -2
+    assert f(2**31, 0, 2, 0, None, ctypes.byref(n)) == -2
+
+
+def _shape(**kw):
+    base = dict(dtype=B.CP_BF16, head_dim=128, n_q_heads=16, n_kv_heads=1, total_q=64,
+                total_kv=256, batch=1, softmax_scale=0.0)
+    base.update(kw)
+    return B.make_shape(**base)
+
+
+def _partial(lib, shape, q=0x1000, k=0x1000, v=0x1000, qp=0x1000, kp=0x1000, cq=None, ck=None,
+             out=0x1000, lse=0x1000, odt=B.CP_FP32, ws=0x1000, wsn=1 << 40):
+    return lib.cp_attn_partial(ctypes.byref(shape), q, k, v, qp, kp, cq, ck, out, lse, odt, ws,
+                               wsn, None)
+
+
+def test_partial_validates_before_launching(lib):
+    # none of these may reach the device: the fake pointers would fault if dereferenced
+    assert lib.cp_attn_partial(None, 1, 1, 1, 1, 1, None, None, 1, 1, 0, None, 0, None) == -1
+    assert _partial(lib, _shape(head_dim=96)) == -3
+    assert _partial(lib, _shape(dtype=7)) == -3
+    assert _partial(lib, _shape(n_q_heads=6, n_kv_heads=4)) == -2
+    assert _partial(lib, _shape(n_kv_heads=0)) == -2
+    assert _partial(lib, _shape(total_q=-1)) == -2
+    assert _partial(lib, _shape(batch=0)) == -2
+    assert _partial(lib, _shape(batch=2)) == -2           # batch > 1 without cu_seqlens
+    assert _partial(lib, _shape(softmax_scale=float("nan"))) == -2
+    assert _partial(lib, _shape(), q=None) == -1
+    assert _partial(lib, _shape(), kp=None) == -1
+    assert _partial(lib, _shape(), lse=None) == -1
+    assert _partial(lib, _shape(), cq=0x1000) == -1       # only one of the two cu_seqlens
+    assert _partial(lib, _shape(), odt=5) == -3
+    assert _partial(lib, _shape(), k=0x1008) == -6
+    assert _partial(lib, _shape(), ws=None) == -4
+    assert _partial(lib, _shape(), ws=0x1010) == -4       # not 256-byte aligned
+    assert _partial(lib, _shape(), wsn=16) == -4
+    assert _partial(lib, _shape(total_q=0)) == 0          # nothing to do, nothing launched
+    s = _shape()
+    s.reserved = 1
+    assert _partial(lib, s) == -2
+
+
+def test_decode_validates_before_launching(lib):
+    def dec(shape, cu=0x1000, bid=0x1000, ws=0x1000, wsn=1 << 40, q=0x1000):
+        return lib.cp_attn_decode(ctypes.byref(shape), q, 0x1000, 0x1000, 0x1000, 0x1000, cu, bid,
+                                  0x1000, 0x1000, B.CP_FP32, ws, wsn, None)
+    assert dec(_shape(dtype=B.CP_FP32)) == -3
+    assert dec(_shape(head_dim=64)) == -3
+    assert dec(_shape(n_q_heads=32)) == -3                # group of 32 > 16
+    assert dec(_shape(), cu=None) == -1
+    assert dec(_shape(), bid=None) == -1
+    assert dec(_shape(), ws=None) == -4
+    assert dec(_shape(), wsn=8) == -4
+    assert dec(_shape(), q=0x1004) == -6
+    assert dec(_shape(total_q=0)) == 0
+
+
+def test_merge_validates_before_launching(lib):
+    vp = ctypes.c_void_p
+
+    def mrg(rows=8, d=128, n=2, outs=(0x1000, 0x2000), lses=(0x1000, 0x2000), pdt=B.CP_FP32,
+            out=0x1000, odt=B.CP_BF16):
+        o = (vp * len(outs))(*outs) if outs is not None else None
+        l = (vp * len(lses))(*lses) if lses is not None else None
+        return lib.cp_attn_merge(rows, d, n, o, l, pdt, out, odt, None, None)
+    assert mrg(rows=-1) == -2
+    assert mrg(d=12) == -2
+    assert mrg(d=512) == -2
+    assert mrg(n=0) == -2
+    assert mrg(n=65, outs=(0x1000,) * 65, lses=(0x1000,) * 65) == -2
+    assert mrg(pdt=3) == -3
+    assert mrg(outs=None) == -1
+    assert mrg(outs=(0x1000, None)) == -1
+    assert mrg(out=None) == -1
+    assert mrg(outs=(0x1000, 0x2004)) == -6
+    assert mrg(rows=0) == 0
+
+
+def test_workspace_sizes(lib):
+    # long query shard: only the per-tile position bounds (8 bytes per 64 keys)
+    big = _shape(total_q=8192, total_kv=8192)
+    assert B.cp_workspace_bytes(big, B.CP_WS_PARTIAL) == 128 * 8
+    # short query shard: split over KV, fp32 partial O and LSE per split
+    small = _shape(total_q=64, total_kv=8256)
+    n = B.cp_workspace_bytes(small, B.CP_WS_PARTIAL)
+    assert n > 64 * 16 * 128 * 4
+    # shapes the vector kernel serves need none
+    assert B.cp_workspace_bytes(_shape(dtype=B.CP_FP32, head_dim=64), B.CP_WS_PARTIAL) == 0
+    assert B.cp_workspace_bytes(_shape(head_dim=96), B.CP_WS_PARTIAL) == 0
+    dec = _shape(total_q=32, total_kv=163840, batch=32)
+    assert B.cp_workspace_bytes(dec, B.CP_WS_DECODE) >= 32 * 16 * 128 * 4
+    assert B.cp_workspace_bytes(dec, B.CP_WS_MERGE) == 0
+
+
+def test_ring_descriptor_validation(lib):
+    d = B.cp_ring_desc()
+    assert lib.cp_ring_passkv(None, None) == -1
+    d.n_ranks = 0
+    assert lib.cp_ring_passkv(ctypes.byref(d), None) == -2
+    d.n_ranks = 2
+    assert lib.cp_ring_passkv(ctypes.byref(d), None) == -1   # per-rank arrays missing
+    assert lib.cp_ring_passq(ctypes.byref(d), None) == -1
+    assert lib.cp_ring_passq_decode(ctypes.byref(d), None) == -1
+    assert lib.cp_ring_workspace_bytes(ctypes.byref(d), 0) == 0
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2411_01783_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text, f
+                assert "cp_oracle" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2411_01783_amd" not in text and "cp_attn.h" not in text, f
