@@ -1,0 +1,343 @@
+"""GPU parity: every entry point of the C-ABI library against the fp64 oracle, element by
+element on the same seeded inputs, at sizes the oracle finishes in seconds that still span
+several tiles and ragged tails. All calls go through the ctypes binding of the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import (LSE_RTOL_FP32, O_ATOL_FP32, check, dev, i32, randn)
+from paper_2411_01783_amd import binding as B
+from paper_2411_01783_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    B.load()  # raises if the HIP library is missing: no fallback
+    assert torch.cuda.is_available()
+
+
+def gpu_partial(q, k, v, qp, kp, **kw):
+    o, l = B.cp_attn_partial(dev(q), dev(k), dev(v), i32(qp), i32(kp), **kw)
+    torch.cuda.synchronize()
+    return o, l
+
+
+# ---------------------------------------------------------------------------
+# tiny pass-KV ring (fp32, d=64, GQA 4:1, 2 virtual ranks over 4 chunks of 128)
+# ---------------------------------------------------------------------------
+
+def test_tiny_passkv_ring_fp32(oracle):
+    w = W.WORKLOADS["tiny_passkv"]
+    q, k, v = W.qkv(w)
+    q64, k64, v64 = W.to_f64(q), W.to_f64(k), W.to_f64(v)
+    n = w.n_ranks
+    pos = [B.cp_shard_positions(w.t_new, n, r) for r in range(n)]
+    np.testing.assert_array_equal(pos[0], np.r_[0:128, 384:512])
+    ref_o, ref_l = oracle.unsharded_causal(q64, k64, v64)
+    o_o, o_l, po, pl = oracle.ring_passkv([q64[p] for p in pos], [k64[p] for p in pos],
+                                          [v64[p] for p in pos], pos, pos)
+    ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                  [i32(p) for p in pos], [i32(p) for p in pos], keep_partials=True)
+    out, lse = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    for a in range(n):
+        for b in range(n):
+            check(*ring.partial(a, b), po[a][b], pl[a][b], O_ATOL_FP32, LSE_RTOL_FP32,
+                  "partial %d,%d" % (a, b))
+        check(out[a], lse[a], ref_o[pos[a]], ref_l[pos[a]], O_ATOL_FP32, LSE_RTOL_FP32,
+              "merged rank %d" % a)
+        np.testing.assert_allclose(o_o[a], ref_o[pos[a]], atol=1e-12)
+
+
+@pytest.mark.parametrize("dtype,d,nh,nkv", [("fp32", 128, 2, 2), ("bf16", 64, 8, 2),
+                                            ("fp32", 64, 3, 1)])
+def test_vector_kernel_shapes(oracle, dtype, d, nh, nkv):
+    tq, tkv = 37, 203
+    q, q64 = randn(1, (tq, nh, d), dtype)
+    k, k64 = randn(2, (tkv, nkv, d), dtype)
+    v, v64 = randn(3, (tkv, nkv, d), dtype)
+    rng = np.random.default_rng(4)
+    qp = rng.integers(-1, 260, size=tq)
+    kp = rng.permutation(300)[:tkv]
+    ref = oracle.attn(q64, k64, v64, qp, kp)
+    o, l = gpu_partial(q, k, v, qp, kp, out_dtype=torch.float32)
+    if dtype == "fp32":
+        check(o, l, *ref, O_ATOL_FP32, LSE_RTOL_FP32)
+    else:
+        check(o, l, *ref)
+
+
+def test_vector_kernel_packed_batch(oracle):
+    cu_q = np.array([0, 5, 5, 40, 41], dtype=np.int32)
+    cu_kv = np.array([0, 70, 90, 90, 300], dtype=np.int32)
+    q, q64 = randn(5, (41, 4, 64), "fp32")
+    k, k64 = randn(6, (300, 2, 64), "fp32")
+    v, v64 = randn(7, (300, 2, 64), "fp32")
+    rng = np.random.default_rng(8)
+    qp, kp = rng.integers(0, 200, size=41), rng.integers(0, 200, size=300)
+    ref = oracle.attn(q64, k64, v64, qp, kp, cu_q=cu_q, cu_kv=cu_kv)
+    o, l = gpu_partial(q, k, v, qp, kp, cu_seqlens_q=i32(cu_q), cu_seqlens_kv=i32(cu_kv))
+    check(o, l, *ref, O_ATOL_FP32, LSE_RTOL_FP32)
+
+
+# ---------------------------------------------------------------------------
+# bf16 MFMA kernel, head_dim 128
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("tq,tkv,nh,nkv", [
+    (300, 777, 16, 1),    # ragged row block (4800 rows) and ragged KV tile (777 = 12*64 + 9)
+    (16, 64, 16, 1),      # exactly one row block, one tile
+    (1, 1, 16, 1),
+    (65, 130, 8, 2),      # two KV heads, group of 4
+    (40, 500, 4, 4),      # MHA: group of 1
+    (33, 257, 24, 1),     # group of 24 (rows of one token straddle wavefronts)
+])
+def test_mfma_partial_random_positions(oracle, tq, tkv, nh, nkv):
+    q, q64 = randn(11, (tq, nh, 128))
+    k, k64 = randn(12, (tkv, nkv, 128))
+    v, v64 = randn(13, (tkv, nkv, 128))
+    rng = np.random.default_rng(14)
+    qp = rng.integers(-1, tkv + 40, size=tq)
+    kp = rng.permutation(tkv + 50)[:tkv]
+    if tkv > 8:
+        kp[rng.integers(0, tkv, size=5)] = B.CP_POS_PAD_KV   # padded slots
+    ref = oracle.attn(q64, k64, v64, qp, kp)
+    for odt in (torch.float32, torch.bfloat16):
+        o, l = gpu_partial(q, k, v, qp, kp, out_dtype=odt)
+        check(o, l, *ref, what="out dtype %s" % odt)
+
+
+def test_mfma_partial_sorted_positions_all_tile_classes(oracle):
+    # natural causal order: tiles are skipped, unmasked, or diagonal depending on the row block
+    t = 700
+    q, q64 = randn(21, (t, 16, 128))
+    k, k64 = randn(22, (t, 1, 128))
+    v, v64 = randn(23, (t, 1, 128))
+    pos = np.arange(t)
+    ref = oracle.attn(q64, k64, v64, pos, pos)
+    o, l = gpu_partial(q, k, v, pos, pos, out_dtype=torch.float32)
+    check(o, l, *ref)
+
+
+def test_mfma_partial_softmax_scale_and_short_rows(oracle):
+    # explicit scale; row 0 sees one key (LSE ~ N(0,1), O = v0 exactly up to bf16 products)
+    t = 130
+    q, q64 = randn(31, (t, 16, 128))
+    k, k64 = randn(32, (t, 1, 128))
+    v, v64 = randn(33, (t, 1, 128))
+    pos = np.arange(t)
+    ref = oracle.attn(q64, k64, v64, pos, pos, scale=0.05)
+    o, l = gpu_partial(q, k, v, pos, pos, out_dtype=torch.float32, softmax_scale=0.05)
+    check(o, l, *ref)
+    np.testing.assert_allclose(o[0].cpu().double().numpy(), np.broadcast_to(v64[0], (16, 128)),
+                               atol=1e-6)
+
+
+@pytest.mark.parametrize("n,t", [(4, 2048), (3, 1000)])
+def test_mfma_load_balanced_partials_and_merge(oracle, n, t):
+    q, q64 = randn(41, (t, 16, 128))
+    k, k64 = randn(42, (t, 1, 128))
+    v, v64 = randn(43, (t, 1, 128))
+    pos = [B.cp_shard_positions(t, n, r) for r in range(n)]
+    ref_o, ref_l = oracle.unsharded_causal(q64, k64, v64)
+    ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                  [i32(p) for p in pos], [i32(p) for p in pos], keep_partials=True,
+                  out_dtype=torch.float32)
+    out, lse = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    for a in range(n):
+        for b in range(n):
+            po, pl = oracle.attn(q64[pos[a]], k64[pos[b]], v64[pos[b]], pos[a], pos[b])
+            check(*ring.partial(a, b), po, pl, what="partial %d,%d" % (a, b))
+        check(out[a], lse[a], ref_o[pos[a]], ref_l[pos[a]], what="merged rank %d" % a)
+    # pass-Q order over the same shards gives the same merged result
+    ring_q = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                    [i32(p) for p in pos], [i32(p) for p in pos], out_dtype=torch.float32)
+    out_q, lse_q = B.cp_ring_passq(ring_q)
+    torch.cuda.synchronize()
+    for a in range(n):
+        check(out_q[a], lse_q[a], ref_o[pos[a]], ref_l[pos[a]], what="pass-Q rank %d" % a)
+
+
+def test_mfma_split_kv_short_query_shard(oracle):
+    # 40 query tokens x 16 heads (3 row blocks) against 3000 keys: the KV axis is split
+    tq, tkv = 40, 3000
+    shape = B.make_shape(B.CP_BF16, 128, 16, 1, tq, tkv)
+    assert B.cp_workspace_bytes(shape, B.CP_WS_PARTIAL) > tq * 16 * 128 * 4 * 2
+    q, q64 = randn(51, (tq, 16, 128))
+    k, k64 = randn(52, (tkv, 1, 128))
+    v, v64 = randn(53, (tkv, 1, 128))
+    qp = np.arange(tkv - tq, tkv)
+    qp[3] = B.CP_POS_PAD_Q
+    kp = np.arange(tkv)
+    ref = oracle.attn(q64, k64, v64, qp, kp)
+    for odt in (torch.float32, torch.bfloat16):
+        o, l = gpu_partial(q, k, v, qp, kp, out_dtype=odt)
+        check(o, l, *ref)
+
+
+def test_partial_degenerate_inputs(oracle):
+    q, q64 = randn(61, (20, 16, 128))
+    k, k64 = randn(62, (100, 1, 128))
+    v, v64 = randn(63, (100, 1, 128))
+    # no keys at all
+    o, l = B.cp_attn_partial(dev(q), dev(k[:0]), dev(v[:0]), i32(np.arange(20)), i32([]),
+                             out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.all(o == 0) and torch.all(torch.isneginf(l))
+    # every key beyond every query
+    o, l = gpu_partial(q, k, v, np.arange(20), np.arange(100) + 1000, out_dtype=torch.float32)
+    assert torch.all(o == 0) and torch.all(torch.isneginf(l))
+    # no queries
+    o, l = B.cp_attn_partial(dev(q[:0]), dev(k), dev(v), i32([]), i32(np.arange(100)))
+    assert o.shape == (0, 16, 128)
+
+
+# ---------------------------------------------------------------------------
+# merge (Equation 4)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n_parts", [1, 2, 3, 16, 17])
+@pytest.mark.parametrize("pdt", [torch.float32, torch.bfloat16])
+def test_merge_matches_oracle(oracle, n_parts, pdt):
+    rows, d = (37, 16), 128
+    rng = np.random.default_rng(70 + n_parts)
+    outs = [torch.from_numpy(rng.standard_normal(rows + (d,))).to(pdt) for _ in range(n_parts)]
+    lses = [rng.standard_normal(rows) * 4 for _ in range(n_parts)]
+    for s in range(n_parts):
+        lses[s][rng.integers(0, rows[0], 6), rng.integers(0, rows[1], 6)] = -np.inf
+    for s in range(n_parts):
+        lses[s][5, :] = -np.inf                       # a row that is empty in every partial
+        outs[s][lses_mask(lses[s])] = float("nan")    # O of an empty partial must not be read
+    ref_o, ref_l = oracle.merge([W.to_f64(o) for o in outs], lses)
+    for odt in (torch.float32, torch.bfloat16):
+        o, l = B.cp_attn_merge([dev(x) for x in outs], [dev(x, torch.float32) for x in lses],
+                               out_dtype=odt)
+        torch.cuda.synchronize()
+        check(o, l, ref_o, ref_l, o_atol=1e-5 if odt == torch.float32 else 2e-2,
+              lse_rtol=1e-5)
+
+
+def lses_mask(l):
+    return torch.from_numpy(np.isneginf(l))
+
+
+def test_merge_large_stream(oracle):
+    # enough rows for the grid-stride loop to wrap (more than 8192 workgroups of 256 slices)
+    rows, d, n = 70001, 128, 4
+    rng = np.random.default_rng(81)
+    outs = [torch.from_numpy(rng.standard_normal((rows, d)).astype(np.float32)) for _ in range(n)]
+    lses = [rng.standard_normal(rows).astype(np.float32) for _ in range(n)]
+    ref_o, ref_l = oracle.merge([x.numpy() for x in outs], lses)
+    o, l = B.cp_attn_merge([dev(x) for x in outs], [dev(x) for x in lses])
+    torch.cuda.synchronize()
+    check(o, l, ref_o, ref_l, o_atol=1e-5, lse_rtol=1e-5)
+
+
+# ---------------------------------------------------------------------------
+# split-KV decode (Algorithm 4)
+# ---------------------------------------------------------------------------
+
+def _decode_case(oracle, lengths, nh, nkv, bid, seed, pad_some=False):
+    total = int(np.sum(lengths))
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    nq = len(bid)
+    q, q64 = randn(seed, (nq, nh, 128))
+    k, k64 = randn(seed + 1, (total, nkv, 128))
+    v, v64 = randn(seed + 2, (total, nkv, 128))
+    kp = np.concatenate([np.arange(n) for n in lengths]).astype(np.int32)
+    qp = np.array([max(lengths[b] - 1, 0) for b in bid], dtype=np.int32)
+    if pad_some:
+        rng = np.random.default_rng(seed)
+        kp[rng.integers(0, total, size=7)] = B.CP_POS_PAD_KV
+        qp[0] = lengths[bid[0]] // 2          # a query that sees only half of its segment
+    segs = [np.arange(cu[b], cu[b + 1]) for b in bid]
+    idx = np.concatenate(segs)
+    cu_sel = np.concatenate([[0], np.cumsum([len(s) for s in segs])]).astype(np.int32)
+    ref = oracle.attn(q64, k64[idx], v64[idx], qp, kp[idx],
+                      cu_q=np.arange(nq + 1, dtype=np.int32), cu_kv=cu_sel)
+    for odt in (torch.float32, torch.bfloat16):
+        o, l = B.cp_attn_decode(dev(q), dev(k), dev(v), i32(qp), i32(kp), i32(cu), i32(bid),
+                                out_dtype=odt)
+        torch.cuda.synchronize()
+        check(o, l, *ref, what="decode out %s" % odt)
+
+
+def test_decode_varied_lengths(oracle):
+    _decode_case(oracle, [1000, 1, 33, 4097, 0, 260, 129], 16, 1, [0, 1, 2, 3, 4, 5, 6], 90)
+
+
+def test_decode_subset_of_sequences_permuted(oracle):
+    _decode_case(oracle, [500, 900, 64, 2000, 31], 16, 1, [3, 0, 3, 4], 93, pad_some=True)
+
+
+def test_decode_smaller_groups(oracle):
+    _decode_case(oracle, [300, 700, 1500], 8, 2, [2, 0, 1], 96)
+    _decode_case(oracle, [300, 700], 4, 4, [1, 0], 99)
+
+
+def test_ring_passq_decode_driver(oracle):
+    n, nh = 4, 16
+    lengths = [900, 35, 2300, 1, 640, 1200, 77, 3000]
+    rng = np.random.default_rng(101)
+    ks = [W.normal(200 + b, (L, 1, 128)) for b, L in enumerate(lengths)]
+    vs = [W.normal(300 + b, (L, 1, 128)) for b, L in enumerate(lengths)]
+    qs = [W.normal(400 + b, (1, nh, 128)) for b in range(len(lengths))]
+    ranks = oracle.shard_decode_batch(lengths, n, decode_iter=1)
+
+    def gather(src, r):
+        if len(r["kv_pos"]) == 0:
+            return torch.zeros((0, 1, 128), dtype=torch.bfloat16)
+        return torch.cat([src[b][p][None] for b, p in zip(r["kv_seq"], r["kv_pos"])])
+    rk = [gather(ks, r) for r in ranks]
+    rv = [gather(vs, r) for r in ranks]
+    rq = [torch.cat([qs[b] for b in r["bid"]]) if len(r["bid"]) else
+          torch.zeros((0, nh, 128), dtype=torch.bfloat16) for r in ranks]
+    ref_o, ref_l, _, _ = oracle.ring_passq_decode(
+        [W.to_f64(x) for x in rq], [r["bid"] for r in ranks], [r["q_pos"] for r in ranks],
+        [W.to_f64(x) for x in rk], [W.to_f64(x) for x in rv], [r["kv_pos"] for r in ranks],
+        [r["cu_kv"] for r in ranks])
+    for keep in (False, True):
+        ring = B.Ring([dev(x) for x in rq], [dev(x) for x in rk], [dev(x) for x in rv],
+                      [i32(r["q_pos"]) for r in ranks], [i32(r["kv_pos"]) for r in ranks],
+                      out_dtype=torch.float32, keep_partials=keep,
+                      cu_seqlens_kv=[i32(r["cu_kv"]) for r in ranks],
+                      bid=[i32(r["bid"]) for r in ranks])
+        out, lse = B.cp_ring_passq_decode(ring)
+        torch.cuda.synchronize()
+        for s in range(n):
+            check(out[s], lse[s], ref_o[s], ref_l[s], what="decode ring rank %d" % s)
+    # and against plain attention of every sequence on its own
+    for s, r in enumerate(ranks):
+        for i, b in enumerate(r["bid"]):
+            L = lengths[b]
+            o1, l1 = oracle.attn(W.to_f64(qs[b]), W.to_f64(ks[b]), W.to_f64(vs[b]), [L - 1],
+                                 np.arange(L))
+            np.testing.assert_allclose(ref_o[s][i], o1[0], atol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# pass-Q partial prefill driver (Algorithm 3) with a cached prefix
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("partition", ["balanced", "contiguous"])
+def test_ring_passq_partial_prefill(oracle, partition):
+    n, p_cached, t_new = 4, 3000, 200
+    q, q64 = randn(111, (t_new, 16, 128))
+    k, k64 = randn(112, (p_cached + t_new, 1, 128))
+    v, v64 = randn(113, (p_cached + t_new, 1, 128))
+    ref_o, ref_l = oracle.unsharded_causal(q64, k64, v64, p_cached=p_cached)
+    sh = oracle.shard_partial_prefill(p_cached, t_new, n, cache_partition=partition)
+    ring = B.Ring([dev(q[qp - p_cached]) for qp, _ in sh], [dev(k[kp]) for _, kp in sh],
+                  [dev(v[kp]) for _, kp in sh], [i32(qp) for qp, _ in sh],
+                  [i32(kp) for _, kp in sh], out_dtype=torch.float32)
+    out, lse = B.cp_ring_passq(ring)
+    torch.cuda.synchronize()
+    for r, (qp, _) in enumerate(sh):
+        check(out[r], lse[r], ref_o[qp - p_cached], ref_l[qp - p_cached], what="rank %d" % r)
+    out2, lse2 = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    for r, (qp, _) in enumerate(sh):
+        check(out2[r], lse2[r], ref_o[qp - p_cached], ref_l[qp - p_cached])
