@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-rank hot path of context-parallel ring attention on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic input: for the
+default workload (Llama3-405B per-GPU head shape, 128K full prefill, pass-KV) that is the
+complete ring of Algorithm 2 over all 16 virtual CP ranks: 16 x (16 partial-attention calls
+on load-balanced shards + 1 merge). Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line. `value` is causal-effective TFLOP/s (4 * d * N_H * visible pairs).
+`roofline` describes the dominant kernel (the bf16 MFMA partial-attention kernel), timed
+with HIP events around every partial-attention call in a second pass over the same ring.
+`cpu_baseline` times the fp64 oracle on a bounded sample of the same workload.
+`aux` carries the bandwidth-bound parts (merge, split-KV decode) in GB/s.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2411_01783_amd import binding as B  # noqa: E402
+from paper_2411_01783_amd import workloads as W  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+
+def _i32(x):
+    return torch.as_tensor(np.asarray(x, dtype=np.int32)).to("cuda")
+
+
+def visible_pairs(q_pos: np.ndarray, kv_pos: np.ndarray) -> int:
+    """Exact count of (query, key) pairs with kv_pos <= q_pos."""
+    ks = np.sort(kv_pos.astype(np.int64))
+    return int(np.searchsorted(ks, q_pos.astype(np.int64), side="right").sum())
+
+
+# ---------------------------------------------------------------------------
+# pass-KV prefill (the headline workload)
+# ---------------------------------------------------------------------------
+
+def build_prefill(w: W.Workload):
+    q, k, v = W.qkv(w, device="cuda")
+    n = w.n_ranks
+    pos = [B.cp_shard_positions(w.t_new, n, r) for r in range(n)]
+    idx = [torch.as_tensor(p.astype(np.int64)).to("cuda") for p in pos]
+    qs = [q[i].contiguous() for i in idx]
+    ks = [k[i].contiguous() for i in idx]
+    vs = [v[i].contiguous() for i in idx]
+    del q
+    ps = [_i32(p) for p in pos]
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
+    return dict(ring=ring, pos=pos, qs=qs, ks=ks, vs=vs, ps=ps, k_full=k, v_full=v)
+
+
+def time_steps(fn, steps: int, warmup: int) -> float:
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
+    """HIP-event time of every partial-attention call of the given ranks' ring loops."""
+    n = w.n_ranks
+    ring = st["ring"]
+    total_ms, total_flop, n_launch = 0.0, 0.0, 0
+    merge_ms, merge_bytes = 0.0, 0.0
+    ws = ring.workspace
+    for kq in ranks:
+        evs = []
+        for j in range(n):
+            s = (kq - j) % n
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            B.cp_attn_partial(st["qs"][kq], st["ks"][s], st["vs"][s], st["ps"][kq], st["ps"][s],
+                              out=ring.partial_out[s], lse=ring.partial_lse[s], workspace=ws)
+            e1.record()
+            evs.append((e0, e1, s))
+        m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        m0.record()
+        B.cp_attn_merge([ring.partial_out[s] for s in range(n)],
+                        [ring.partial_lse[s] for s in range(n)], out=ring.out[kq],
+                        lse_out=ring.lse[kq])
+        m1.record()
+        torch.cuda.synchronize()
+        for e0, e1, s in evs:
+            total_ms += e0.elapsed_time(e1)
+            total_flop += 4.0 * w.head_dim * w.n_q_heads * visible_pairs(st["pos"][kq],
+                                                                         st["pos"][s])
+            n_launch += 1
+        merge_ms += m0.elapsed_time(m1)
+        rows = ring.out[kq].shape[0] * w.n_q_heads
+        merge_bytes += n * rows * (w.head_dim * 4 + 4) + rows * (w.head_dim * 2 + 4)
+    return dict(ms_per_launch=total_ms / n_launch, flop_per_launch=total_flop / n_launch,
+                n_launch=n_launch, merge_ms=merge_ms / len(ranks),
+                merge_bytes=merge_bytes / len(ranks))
+
+
+def cpu_baseline_prefill(w: W.Workload, st: dict, n_tokens: int = 1024):
+    """fp64 oracle on a seeded sample of query tokens of the same sequence (all heads)."""
+    import oracle
+    rng = np.random.default_rng(w.seed)
+    tok = np.sort(rng.choice(w.t_new, size=n_tokens, replace=False))
+    k64 = W.to_f64(st["k_full"])
+    v64 = W.to_f64(st["v_full"])
+    # the sampled query rows: regenerate the same seeded q on the device, copy the rows
+    q_full, _, _ = W.qkv(w, device="cuda", n_kv=1)
+    q64 = W.to_f64(q_full[torch.as_tensor(tok).to("cuda")])
+    del q_full
+    t0 = time.perf_counter()
+    _, _, pairs = oracle.attn(q64, k64, v64, tok, np.arange(w.t_new), return_pairs=True)
+    dt = time.perf_counter() - t0
+    flop = 4.0 * w.head_dim * w.n_q_heads * pairs
+    return dict(value=flop / dt / 1e12, unit="TFLOP/s", cores=oracle.num_threads(), kind="oracle",
+                sample="%d seeded query tokens x %d heads vs all visible keys of the %d-token "
+                       "sequence (%.2e pairs, %.1f s)" % (n_tokens, w.n_q_heads, w.t_new,
+                                                          pairs, dt))
+
+
+# ---------------------------------------------------------------------------
+# split-KV decode (aux; HBM-bound)
+# ---------------------------------------------------------------------------
+
+def build_decode(w: W.Workload):
+    lengths = W.decode_lengths(w)
+    n = w.n_ranks
+    ranks = []
+    for r in range(n):
+        pos, cu = [], [0]
+        for b, L in enumerate(lengths):
+            p = B.cp_shard_positions(int(L) - 1, n, r)
+            if b % n == r:  # round-robin owner of the new token (decode iteration 0)
+                p = np.concatenate([p, np.array([L - 1], dtype=np.int32)])
+            pos.append(p)
+            cu.append(cu[-1] + len(p))
+        total = cu[-1]
+        ranks.append(dict(
+            k=W.normal(w.seed * 100 + 2 * r, (total, w.n_kv_heads, w.head_dim), w.dtype, "cuda"),
+            v=W.normal(w.seed * 100 + 2 * r + 1, (total, w.n_kv_heads, w.head_dim), w.dtype,
+                       "cuda"),
+            kv_pos=_i32(np.concatenate(pos)), cu=_i32(cu), total=total))
+    q = W.normal(w.seed * 100 + 99, (w.batch, w.n_q_heads, w.head_dim), w.dtype, "cuda")
+    q_pos = _i32(lengths - 1)
+    bid = _i32(np.arange(w.batch))
+    return dict(ranks=ranks, q=q, q_pos=q_pos, bid=bid, lengths=lengths)
+
+
+def bench_decode(w: W.Workload, reps: int = 20):
+    st = build_decode(w)
+    n = w.n_ranks
+    shape = B.make_shape(B.CP_BF16, w.head_dim, w.n_q_heads, w.n_kv_heads, w.batch,
+                         max(r["total"] for r in st["ranks"]), w.batch)
+    ws = torch.empty(B.cp_workspace_bytes(shape, B.CP_WS_DECODE) + 256, dtype=torch.uint8,
+                     device="cuda")
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    lse = torch.empty((w.batch, w.n_q_heads), dtype=torch.float32, device="cuda")
+
+    def one_pass():
+        # every virtual rank's whole ring loop in one launch: all 32 queries against its KV
+        for r in st["ranks"]:
+            B.cp_attn_decode(st["q"], r["k"], r["v"], st["q_pos"], r["kv_pos"], r["cu"],
+                             st["bid"], out=out, lse=lse, workspace=ws)
+    sec = time_steps(one_pass, reps, 3)
+    kv_bytes = sum(2 * r["total"] * w.n_kv_heads * w.head_dim * 2 for r in st["ranks"])
+    io_bytes = n * (st["q"].numel() * 2 + out.numel() * 4 + lse.numel() * 4)
+    return dict(workload=w.name, ms_per_rank=sec * 1e3 / n, gbs=(kv_bytes + io_bytes) / sec / 1e9,
+                frac_hbm=(kv_bytes + io_bytes) / sec / 1e9 / PEAK_HBM_GBS,
+                kv_mb_per_rank=kv_bytes / n / 1e6)
+
+
+# ---------------------------------------------------------------------------
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="prefill_128k",
+                    choices=["prefill_128k", "prefill_1m"])
+    ap.add_argument("--no-aux", action="store_true", help="skip the decode measurement")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the ring is simulated over virtual CP ranks on a "
+              "single MI355X and no multi-GPU path exists in this build (got --gpus %d)"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    B.load()
+
+    w = W.WORKLOADS[args.workload]
+    st = build_prefill(w)
+    ring = st["ring"]
+    sec = time_steps(lambda: B.cp_ring_passkv(ring), args.steps, args.warmup)
+    t = w.t_new
+    flop_step = 4.0 * w.head_dim * w.n_q_heads * (t * (t + 1) // 2)
+    tflops = flop_step / sec / 1e12
+
+    kp = kernel_pass_prefill(w, st, ranks=[0, w.n_ranks // 2, w.n_ranks - 1])
+    achieved = kp["flop_per_launch"] / (kp["ms_per_launch"] * 1e-3) / 1e12
+    result = {
+        "metric": "per-rank partial-attn+merge TFLOP/s (% bf16 MFMA peak); decode HBM GB/s",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 3), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "order": "pass-KV", "virtual_ranks": w.n_ranks,
+                   "tokens": t, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "partial_dtype": "fp32",
+                   "flops": "causal-effective 4*d*N_H*pairs",
+                   "ms_per_rank": round(sec * 1e3 / w.n_ranks, 3)},
+        "frac_of_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
+        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel",
+                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "us_per_launch": round(kp["ms_per_launch"] * 1e3, 2),
+                     "flop_per_launch": kp["flop_per_launch"], "launches": kp["n_launch"]},
+        "aux": {"merge": {"ms": round(kp["merge_ms"], 4),
+                          "gbs": round(kp["merge_bytes"] / (kp["merge_ms"] * 1e-3) / 1e9, 1),
+                          "frac_hbm": round(kp["merge_bytes"] / (kp["merge_ms"] * 1e-3) / 1e9 /
+                                            PEAK_HBM_GBS, 4)}},
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline_prefill(w, st)
+    del st, ring
+    torch.cuda.empty_cache()
+    if not args.no_aux:
+        d = bench_decode(W.WORKLOADS["decode_b32"])
+        result["aux"]["decode"] = {k: (round(v, 4) if isinstance(v, float) else v)
+                                   for k, v in d.items()}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -110,7 +110,7 @@ int cp_attn_partial(const cp_shape* shape, const void* q, const void* k, const v
     if (need > 0 && (workspace == nullptr || !aligned256(workspace) || workspace_bytes < need))
       return CP_ERR_WORKSPACE;
     return launch_prefill_mfma(s, scale, q, k, v, q_pos, kv_pos, out, lse, out_dtype, workspace,
-                               workspace_bytes, st);
+                               workspace_bytes, nullptr, st);
   }
   return launch_partial_generic(s, scale, q, k, v, q_pos, kv_pos, cu_seqlens_q, cu_seqlens_kv,
                                 out, lse, out_dtype, st);
@@ -211,6 +211,20 @@ static cp_shape ring_shape(const cp_ring_desc* d, int q_rank, int kv_rank, bool 
   return s;
 }
 
+// Ring workspace layout: the per-tile kv_pos bounds of every rank's KV shard (computed once
+// per driver call, reused by the N calls that read the shard), then the per-call workspace.
+static bool ring_uses_tile_bounds(const cp_ring_desc* d, bool decode) {
+  cp_shape s = ring_shape(d, 0, 0, decode);
+  return !decode && mfma_prefill_applies(s);
+}
+
+static size_t ring_bounds_bytes(const cp_ring_desc* d, bool decode) {
+  if (!ring_uses_tile_bounds(d, decode)) return 0;
+  size_t total = 0;
+  for (int b = 0; b < d->n_ranks; ++b) total += kv_tile_bounds_bytes(d->n_kv[b]);
+  return total;
+}
+
 extern "C" size_t cp_ring_workspace_bytes(const cp_ring_desc* d, int32_t decode) {
   if (check_ring(d, decode != 0) != CP_OK) return 0;
   size_t need = 0;
@@ -219,7 +233,7 @@ extern "C" size_t cp_ring_workspace_bytes(const cp_ring_desc* d, int32_t decode)
       cp_shape s = ring_shape(d, a, b, decode != 0);
       need = std::max(need, cp_workspace_bytes(&s, decode ? CP_WS_DECODE : CP_WS_PARTIAL));
     }
-  return need;
+  return need + ring_bounds_bytes(d, decode != 0);
 }
 
 namespace {
@@ -244,16 +258,50 @@ RingSlots make_slots(const cp_ring_desc* d) {
   return r;
 }
 
+struct RingWork {
+  bool use_bounds = false;
+  size_t bounds_off[CP_MAX_PARTS] = {};
+  char* call_ws = nullptr;
+  size_t call_ws_bytes = 0;
+};
+
+// Checks the workspace and, for the MFMA path, records the tile bounds of every KV shard.
+int ring_prepare(const cp_ring_desc* d, bool decode, hipStream_t st, RingWork& w) {
+  const size_t need = cp_ring_workspace_bytes(d, decode ? 1 : 0);
+  if (need > 0 && (d->workspace == nullptr || !aligned256(d->workspace) ||
+                   d->workspace_bytes < need))
+    return CP_ERR_WORKSPACE;
+  w.use_bounds = ring_uses_tile_bounds(d, decode);
+  size_t off = 0;
+  if (w.use_bounds) {
+    for (int b = 0; b < d->n_ranks; ++b) {
+      w.bounds_off[b] = off;
+      if (launch_kv_tile_bounds(d->kv_pos[b], d->n_kv[b], (char*)d->workspace + off, st) != CP_OK)
+        return CP_ERR_LAUNCH;
+      off += kv_tile_bounds_bytes(d->n_kv[b]);
+    }
+  }
+  w.call_ws = (char*)d->workspace + off;
+  w.call_ws_bytes = d->workspace_bytes >= off ? d->workspace_bytes - off : 0;
+  return CP_OK;
+}
+
 // One partial-attention call of the ring: queries of rank `a` against KV of rank `b`.
-int ring_partial(const cp_ring_desc* d, bool decode, int a, int b, void* o, float* l,
-                 hipStream_t st) {
+int ring_partial(const cp_ring_desc* d, const RingWork& w, bool decode, int a, int b, void* o,
+                 float* l, hipStream_t st) {
   cp_shape s = ring_shape(d, a, b, decode);
   if (decode)
     return cp_attn_decode(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b],
-                          d->cu_seqlens_kv[b], d->bid[a], o, l, d->part_dtype, d->workspace,
-                          d->workspace_bytes, st);
+                          d->cu_seqlens_kv[b], d->bid[a], o, l, d->part_dtype, w.call_ws,
+                          w.call_ws_bytes, st);
+  if (w.use_bounds && s.total_q > 0) {
+    if (!aligned16(d->q[a]) || !aligned16(d->k[b]) || !aligned16(d->v[b])) return CP_ERR_ALIGN;
+    return launch_prefill_mfma(s, resolve_scale(s.softmax_scale, s.head_dim), d->q[a], d->k[b],
+                               d->v[b], d->q_pos[a], d->kv_pos[b], o, l, d->part_dtype, w.call_ws,
+                               w.call_ws_bytes, (char*)d->workspace + w.bounds_off[b], st);
+  }
   return cp_attn_partial(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b], nullptr,
-                         nullptr, o, l, d->part_dtype, d->workspace, d->workspace_bytes, st);
+                         nullptr, o, l, d->part_dtype, w.call_ws, w.call_ws_bytes, st);
 }
 
 int ring_merge(const cp_ring_desc* d, const RingSlots& slots, int a, int64_t first_slot,
@@ -279,12 +327,15 @@ int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const RingSlots slots = make_slots(d);
   const int n = d->n_ranks;
+  RingWork w;
+  rc = ring_prepare(d, false, st, w);
+  if (rc != CP_OK) return rc;
   // Algorithm 2 as seen from each rank k in turn: N ring steps, then a local merge.
   for (int k = 0; k < n; ++k) {
     const int64_t base = d->keep_partials ? (int64_t)k * n : 0;
     for (int j = 0; j < n; ++j) {
       const int s = ((k - j) % n + n) % n;  // origin rank of the KV held at step j
-      rc = ring_partial(d, false, k, s, slots.out(base + s), slots.lse(base + s), st);
+      rc = ring_partial(d, w, false, k, s, slots.out(base + s), slots.lse(base + s), st);
       if (rc != CP_OK) return rc;
     }
     rc = ring_merge(d, slots, k, base, st);
@@ -299,13 +350,16 @@ static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
   hipStream_t st = (hipStream_t)stream;
   const RingSlots slots = make_slots(d);
   const int n = d->n_ranks;
+  RingWork w;
+  rc = ring_prepare(d, decode, st, w);
+  if (rc != CP_OK) return rc;
   if (d->keep_partials) {
     // Algorithms 3 / 4 in ring order: at step j rank k holds the queries of rank
     // s = (k - j) mod N. Writing the result to slot [s][k] is the permute + All2All.
     for (int j = 0; j < n; ++j)
       for (int k = 0; k < n; ++k) {
         const int s = ((k - j) % n + n) % n;
-        rc = ring_partial(d, decode, s, k, slots.out((int64_t)s * n + k),
+        rc = ring_partial(d, w, decode, s, k, slots.out((int64_t)s * n + k),
                           slots.lse((int64_t)s * n + k), st);
         if (rc != CP_OK) return rc;
       }
@@ -321,7 +375,7 @@ static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
   for (int s = 0; s < n; ++s) {
     for (int j = 0; j < n; ++j) {
       const int k = (s + j) % n;
-      rc = ring_partial(d, decode, s, k, slots.out(k), slots.lse(k), st);
+      rc = ring_partial(d, w, decode, s, k, slots.out(k), slots.lse(k), st);
       if (rc != CP_OK) return rc;
     }
     rc = ring_merge(d, slots, s, 0, st);

@@ -42,11 +42,17 @@ int launch_partial_generic(const cp_shape& s, float scale, const void* q, const 
                            int32_t out_dtype, hipStream_t stream);
 
 // bf16 MFMA kernel, head_dim 128, batch 1.
+// `tile_bounds`, when not NULL, holds the per-tile (min, max) of kv_pos already computed by
+// launch_kv_tile_bounds for this kv_pos array; otherwise the launcher computes it into the
+// workspace first.
 size_t prefill_mfma_workspace_bytes(const cp_shape& s);
+size_t kv_tile_bounds_bytes(int64_t total_kv);
+int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_out,
+                          hipStream_t stream);
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
-                        hipStream_t stream);
+                        const void* tile_bounds, hipStream_t stream);
 
 // split-KV decode, bf16, head_dim 128.
 size_t decode_workspace_bytes(const cp_shape& s);

@@ -352,10 +352,23 @@ size_t prefill_mfma_workspace_bytes(const cp_shape& s) {
   return pl.bounds_bytes + pl.part_out_bytes + pl.part_lse_bytes;
 }
 
+size_t kv_tile_bounds_bytes(int64_t total_kv) {
+  return round256((size_t)std::max<int64_t>((total_kv + BN - 1) / BN, 1) * sizeof(int2));
+}
+
+int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_out,
+                          hipStream_t stream) {
+  const int n_tiles = (int)((total_kv + BN - 1) / BN);
+  if (n_tiles == 0) return CP_OK;
+  hipLaunchKernelGGL(kv_tile_bounds_kernel, dim3((n_tiles + 3) / 4), dim3(256), 0, stream, kv_pos,
+                     (int32_t)total_kv, n_tiles, (int2*)bounds_out);
+  return check_launch();
+}
+
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
-                        hipStream_t stream) {
+                        const void* tile_bounds, hipStream_t stream) {
   const Plan pl = make_plan(s);
   if (workspace_bytes < pl.bounds_bytes + pl.part_out_bytes + pl.part_lse_bytes)
     return CP_ERR_WORKSPACE;
@@ -366,7 +379,7 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
   Params p;
   p.q = (const bf16_t*)q; p.k = (const bf16_t*)k; p.v = (const bf16_t*)v;
   p.q_pos = q_pos; p.kv_pos = kv_pos;
-  p.bounds = (const int2*)ws;
+  p.bounds = tile_bounds != nullptr ? (const int2*)tile_bounds : (const int2*)ws;
   p.out = out; p.lse = lse;
   p.part_out = (float*)(ws + pl.bounds_bytes);
   p.part_lse = (float*)(ws + pl.bounds_bytes + pl.part_out_bytes);
@@ -380,11 +393,8 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
   p.n_splits = pl.n_splits;
   p.scale_log2 = scale * kLog2e;
 
-  if (pl.n_tiles > 0) {
-    hipLaunchKernelGGL(kv_tile_bounds_kernel, dim3((pl.n_tiles + 3) / 4), dim3(256), 0, stream,
-                       kv_pos, p.total_kv, pl.n_tiles, (int2*)ws);
-    if (check_launch() != CP_OK) return CP_ERR_LAUNCH;
-  }
+  if (tile_bounds == nullptr && launch_kv_tile_bounds(kv_pos, s.total_kv, ws, stream) != CP_OK)
+    return CP_ERR_LAUNCH;
 
   const dim3 grid(pl.n_row_blocks, s.n_kv_heads, pl.n_splits);
   const bool direct_bf16 = pl.n_splits == 1 && out_dtype == CP_BF16;
