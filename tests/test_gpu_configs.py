@@ -1,0 +1,182 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The fp64 oracle cannot brute-force 128K or 1M tokens, so every case compares a seeded sample
+of query tokens (all heads; always including the first and last row of each chunk a rank
+owns) against the oracle's UNSHARDED causal attention of those rows, plus sampled rows of
+individual partial calls against the oracle's partial for the same shard pair."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import check, i32, rel_l2
+from paper_2411_01783_amd import binding as B
+from paper_2411_01783_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(n_rows, chunk, rng, extra=8):
+    """Row indices of one rank's shard: chunk edges plus a seeded random sample."""
+    edges = [0, 1, chunk - 1, chunk, chunk + 1, n_rows - 1]
+    rows = set(int(e) for e in edges if 0 <= e < n_rows)
+    rows.update(int(x) for x in rng.integers(0, n_rows, size=extra))
+    return np.array(sorted(rows))
+
+
+def _gather_f64(t, idx):
+    return W.to_f64(t[torch.as_tensor(np.asarray(idx, dtype=np.int64)).to(t.device)])
+
+
+def _shard(w, q, k, v):
+    n = w.n_ranks
+    pos = [B.cp_shard_positions(w.t_new, n, r) for r in range(n)]
+    idx = [torch.as_tensor(p.astype(np.int64)).to("cuda") for p in pos]
+    return pos, [q[i].contiguous() for i in idx], [k[i].contiguous() for i in idx], \
+        [v[i].contiguous() for i in idx]
+
+
+def test_prefill_128k_passkv_ring_sampled(oracle):
+    w = W.WORKLOADS["prefill_128k"]
+    q, k, v = W.qkv(w, device="cuda")
+    pos, qs, ks, vs = _shard(w, q, k, v)
+    ps = [i32(p) for p in pos]
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
+    out, lse = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    k64, v64 = W.to_f64(k), W.to_f64(v)
+    rng = np.random.default_rng(w.seed)
+    chunk = w.t_new // (2 * w.n_ranks)
+    worst = 0.0
+    for r in (0, 6, 15):
+        rows = _sample_rows(len(pos[r]), chunk, rng)
+        tok = pos[r][rows]
+        ref_o, ref_l = oracle.attn(_gather_f64(q, tok), k64, v64, tok, np.arange(w.t_new))
+        sel = torch.as_tensor(rows).to("cuda")
+        check(out[r][sel], lse[r][sel], ref_o, ref_l, what="rank %d" % r)
+        worst = max(worst, rel_l2(out[r][sel], ref_o))
+    # with long rows |O| ~ 1/sqrt(n) is far below the max-abs bar, so bound the relative error too
+    assert worst < 2e-2, worst
+    # individual partial calls: a diagonal step and the two kinds of off-diagonal step
+    for a, b in ((5, 5), (5, 9), (9, 5)):
+        rows = _sample_rows(len(pos[a]), chunk, rng)
+        o, l = B.cp_attn_partial(qs[a], ks[b], vs[b], ps[a], ps[b], out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        ref_o, ref_l = oracle.attn(_gather_f64(qs[a], rows), W.to_f64(ks[b]),
+                                   W.to_f64(vs[b]), pos[a][rows], pos[b])
+        sel = torch.as_tensor(rows).to("cuda")
+        check(o[sel], l[sel], ref_o, ref_l, what="partial %d,%d" % (a, b))
+    # structure of the step: rows of the early chunk see nothing of a later rank's shard
+    o, l = B.cp_attn_partial(qs[5], ks[9], vs[9], ps[5], ps[9], out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.all(torch.isneginf(l[:chunk])) and torch.all(o[:chunk] == 0)
+    assert torch.all(torch.isfinite(l[chunk:]))
+
+
+def test_prefill_1m_one_rank_sampled(oracle):
+    w = W.WORKLOADS["prefill_1m"]
+    q, k, v = W.qkv(w, device="cuda")
+    n = w.n_ranks
+    r = 3
+    pos = [B.cp_shard_positions(w.t_new, n, s) for s in range(n)]
+    idx = [torch.as_tensor(p.astype(np.int64)).to("cuda") for p in pos]
+    q_r = q[idx[r]].contiguous()
+    nq = q_r.shape[0]
+    part_o = torch.empty((n, nq, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    part_l = torch.empty((n, nq, w.n_q_heads), dtype=torch.float32, device="cuda")
+    for j in range(n):          # Algorithm 2 on rank r
+        s = (r - j) % n
+        B.cp_attn_partial(q_r, k[idx[s]].contiguous(), v[idx[s]].contiguous(), i32(pos[r]),
+                          i32(pos[s]), out=part_o[s], lse=part_l[s])
+    out, lse = B.cp_attn_merge([part_o[s] for s in range(n)], [part_l[s] for s in range(n)],
+                               out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(w.seed)
+    chunk = w.t_new // (2 * n)
+    rows = _sample_rows(nq, chunk, rng, extra=4)
+    tok = pos[r][rows]
+    ref_o, ref_l = oracle.attn(_gather_f64(q, tok), W.to_f64(k), W.to_f64(v), tok,
+                               np.arange(w.t_new))
+    sel = torch.as_tensor(rows).to("cuda")
+    check(out[sel], lse[sel], ref_o, ref_l)
+    assert rel_l2(out[sel], ref_o) < 2e-2
+
+
+@pytest.mark.parametrize("name", ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
+                                  "partial_prefill_128k_t8192"])
+def test_partial_prefill_passq_ring_sampled(oracle, name):
+    w = W.WORKLOADS[name]
+    q, k, v = W.qkv(w, device="cuda")
+    n, p_cached, t_new = w.n_ranks, w.p_cached, w.t_new
+    qpos, kvpos = [], []
+    for r in range(n):
+        qp = B.cp_shard_positions(t_new, n, r, offset=p_cached)
+        qpos.append(qp)
+        kvpos.append(np.concatenate([B.cp_shard_positions(p_cached, n, r), qp]).astype(np.int32))
+
+    def take(t, p):
+        return t[torch.as_tensor(p.astype(np.int64)).to("cuda")].contiguous()
+    ring = B.Ring([take(q, p - p_cached) for p in qpos], [take(k, p) for p in kvpos],
+                  [take(v, p) for p in kvpos], [i32(p) for p in qpos], [i32(p) for p in kvpos],
+                  out_dtype=torch.bfloat16)
+    out, lse = B.cp_ring_passq(ring)
+    torch.cuda.synchronize()
+    k64, v64 = W.to_f64(k), W.to_f64(v)
+    rng = np.random.default_rng(w.seed)
+    for r in range(0, n, 5):
+        nq = len(qpos[r])
+        rows = _sample_rows(nq, nq // 2, rng, extra=4)
+        tok = qpos[r][rows]
+        ref_o, ref_l = oracle.attn(_gather_f64(q, tok - p_cached), k64, v64, tok,
+                                   np.arange(p_cached + t_new))
+        sel = torch.as_tensor(rows).to("cuda")
+        check(out[r][sel], lse[r][sel], ref_o, ref_l, what="rank %d" % r)
+        assert rel_l2(out[r][sel], ref_o) < 2e-2
+
+
+def test_decode_b32_passq_ring_full(oracle):
+    w = W.WORKLOADS["decode_b32"]
+    lengths = W.decode_lengths(w)
+    n = w.n_ranks
+    assert lengths.min() >= w.len_lo and lengths.max() <= w.len_hi
+    ks = [W.normal(w.seed * 1000 + 2 * b, (int(L), 1, w.head_dim), device="cuda")
+          for b, L in enumerate(lengths)]
+    vs = [W.normal(w.seed * 1000 + 2 * b + 1, (int(L), 1, w.head_dim), device="cuda")
+          for b, L in enumerate(lengths)]
+    qs = W.normal(w.seed * 1000 + 999, (w.batch, w.n_q_heads, w.head_dim), device="cuda")
+    rk, rv, rpos, rcu, rbid, rq, rqpos = [], [], [], [], [], [], []
+    for r in range(n):
+        kparts, vparts, pos, cu, bid = [], [], [], [0], []
+        for b, L in enumerate(lengths):
+            p = B.cp_shard_positions(int(L) - 1, n, r)
+            if b % n == r:     # owner of the new token at decode iteration 0
+                p = np.concatenate([p, np.array([L - 1], dtype=np.int32)])
+                bid.append(b)
+            sel = torch.as_tensor(p.astype(np.int64)).to("cuda")
+            kparts.append(ks[b][sel]); vparts.append(vs[b][sel])
+            pos.append(p); cu.append(cu[-1] + len(p))
+        rk.append(torch.cat(kparts).contiguous()); rv.append(torch.cat(vparts).contiguous())
+        rpos.append(i32(np.concatenate(pos))); rcu.append(i32(cu)); rbid.append(i32(bid))
+        rq.append(qs[torch.as_tensor(bid).to("cuda")].contiguous())
+        rqpos.append(i32(lengths[bid] - 1))
+    ring = B.Ring(rq, rk, rv, rqpos, rpos, out_dtype=torch.float32, cu_seqlens_kv=rcu, bid=rbid)
+    out, lse = B.cp_ring_passq_decode(ring)
+    torch.cuda.synchronize()
+    for r in range(n):
+        for i, b in enumerate(rbid[r].cpu().numpy()):
+            L = int(lengths[b])
+            ref_o, ref_l = oracle.attn(W.to_f64(qs[b:b + 1]), W.to_f64(ks[b]), W.to_f64(vs[b]),
+                                       [L - 1], np.arange(L))
+            check(out[r][i:i + 1], lse[r][i:i + 1], ref_o, ref_l, what="sequence %d" % b)
+            assert rel_l2(out[r][i:i + 1], ref_o) < 2e-2
+    # one launch per rank with all 32 queries (the shape bench.py times) gives the same partials
+    allq_pos = i32(lengths - 1)
+    allbid = i32(np.arange(w.batch))
+    o1, l1 = B.cp_attn_decode(qs, rk[2], rv[2], allq_pos, rpos[2], rcu[2], allbid,
+                              out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    b = 5
+    p = np.concatenate([B.cp_shard_positions(int(lengths[b]) - 1, n, 2),
+                        np.array([lengths[b] - 1] if b % n == 2 else [], dtype=np.int32)])
+    ref_o, ref_l = oracle.attn(W.to_f64(qs[b:b + 1]), _gather_f64(ks[b], p), _gather_f64(vs[b], p),
+                               [int(lengths[b]) - 1], p)
+    check(o1[b:b + 1], l1[b:b + 1], ref_o, ref_l, what="rank 2, sequence 5")
