@@ -8,34 +8,53 @@
 //     token-major. The causal mask depends on the token only, so all G heads of
 //     a token share mask and K/V tile: GQA turns into a taller M dimension.
 //   - A workgroup of 8 wavefronts owns 256 consecutive rows, 32 per wavefront,
-//     and walks the KV axis in tiles of 64 keys staged through LDS (double
-//     buffered; K as [key][d], V transposed to [d][key] while it is stored).
+//     and walks the KV axis in tiles of 128 keys staged through LDS (double
+//     buffered; K as [key][d], V transposed to [d][key] while it is stored),
+//     one workgroup barrier per tile. A tile is consumed in two steps of 64 keys.
 //   - Scores are produced transposed, S^T = K Q^T with v_mfma_f32_32x32x16_bf16:
 //     a lane then holds 16 keys of ONE query per 32-key block, so the softmax
 //     row statistics are per-lane scalars (one cross-lane exchange with lane^32)
 //     and the exponentiated block is already in the B-operand layout of the
 //     second product O^T += V^T P^T. No register shuffle between the products.
+//   - The next tile travels HBM/L2 -> registers -> LDS in two halves while the
+//     current one is computed; the LDS stores sit between the softmax and the
+//     second product, when the LDS pipe is otherwise idle.
 //   - Tile skipping (load-balanced sharding leaves half of every off-diagonal
 //     step fully masked): a pre-pass records min/max kv_pos of every KV tile;
-//     a workgroup skips tiles whose smallest position exceeds its largest query
-//     position, and only tiles that straddle a query position pay for the mask.
+//     each workgroup compacts the tiles any of its queries can see into a list
+//     in LDS and walks only those; only tiles that straddle a query position
+//     pay for the mask.
 //   - Short query shards (pass-Q partial prefill) are split over the KV axis
 //     (grid.z); split results go to the workspace and are combined with Eq. 4.
+//   - The epilogue transposes the accumulators through LDS so that every output
+//     row leaves as one contiguous 512-byte (fp32) or 256-byte (bf16) run.
 #include "cp_common.h"
 
 namespace cp {
 namespace {
 
-constexpr int D = 128;         // head_dim
-constexpr int BM = 256;        // rows per workgroup
-constexpr int BN = 64;         // keys per tile
-constexpr int NWAVE = 8;       // wavefronts per workgroup
+constexpr int D = 128;          // head_dim
+constexpr int BM = 256;         // rows per workgroup
+constexpr int TILE = 128;       // keys per LDS tile (one barrier)
+constexpr int SUB = 64;         // keys per compute step
+constexpr int NWAVE = 8;        // wavefronts per workgroup
 constexpr int NTHREADS = NWAVE * 64;
-constexpr int K_STRIDE = D * 2 + 16;   // bytes per key row in LDS (+16: conflict-free b128 reads)
-constexpr int VT_STRIDE = BN * 2 + 16; // bytes per d row of transposed V
-constexpr int K_BYTES = BN * K_STRIDE;
+constexpr int K_STRIDE = D * 2 + 16;      // bytes per key row in LDS (+16: conflict-free b128 reads)
+constexpr int VT_STRIDE = TILE * 2 + 16;  // bytes per channel row of transposed V
+constexpr int K_BYTES = TILE * K_STRIDE;
 constexpr int VT_BYTES = D * VT_STRIDE;
-constexpr int SMEM_BYTES = 2 * K_BYTES + 2 * VT_BYTES + 64;
+constexpr int POS_BYTES = TILE * 4;
+constexpr int MAX_LIVE = 512;   // live-tile list entries per chunk (8 wavefronts x 64 tiles)
+constexpr int OFF_VT = 2 * K_BYTES;
+constexpr int OFF_POS = OFF_VT + 2 * VT_BYTES;
+constexpr int OFF_SCRATCH = OFF_POS + 2 * POS_BYTES;
+constexpr int OFF_LIVE = OFF_SCRATCH + 64;
+constexpr int SMEM_BYTES = OFF_LIVE + MAX_LIVE * 16;
+constexpr int OUT_STRIDE = D * 4 + 16;    // epilogue staging: one fp32 output row + pad
+static_assert(NWAVE * 32 * OUT_STRIDE <= OFF_POS, "epilogue staging aliases the tile buffers");
+static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget of one CU");
+constexpr float kRescaleSlack = 8.f;  // log2 units
+constexpr int kReadAhead = 8;         // LDS fragment reads in flight ahead of their MFMA
 
 struct Params {
   const bf16_t* q;
@@ -65,9 +84,16 @@ __global__ __launch_bounds__(256) void kv_tile_bounds_kernel(const int32_t* __re
   const int tile = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tile >= n_tiles) return;
   const int lane = threadIdx.x & 63;
-  const int idx = tile * BN + lane;
   int lo = INT32_MAX, hi = INT32_MIN;
-  if (idx < total_kv) lo = hi = kv_pos[idx];
+#pragma unroll
+  for (int h = 0; h < TILE / 64; ++h) {
+    const int idx = tile * TILE + h * 64 + lane;
+    if (idx < total_kv) {
+      const int32_t x = kv_pos[idx];
+      lo = min(lo, x);
+      hi = max(hi, x);
+    }
+  }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     lo = min(lo, __shfl_xor(lo, o, 64));
@@ -80,48 +106,94 @@ __device__ __forceinline__ floatx16_t mfma32(bf16x8_t a, bf16x8_t b, floatx16_t 
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
-
-// Global -> register staging of one KV tile (held across the compute of the previous tile).
-struct TileRegs {
-  uint4 k[2];  // 2 x 8 bf16 of K
-  uint2 v[4];  // 4 keys x 4 bf16 of V
-};
-
-__device__ __forceinline__ void load_tile(const Params& p, int kvh, int tile, int tid,
-                                          TileRegs& r) {
-  const int key0 = tile * BN;
-  const int64_t head_off = (int64_t)kvh * D;
-  const int64_t tok_stride = (int64_t)p.n_kv_heads * D;
-#pragma unroll
-  for (int pp = 0; pp < 2; ++pp) {
-    const int key = key0 + pp * 32 + (tid >> 4);
-    r.k[pp] = make_uint4(0, 0, 0, 0);
-    if (key < p.total_kv)
-      r.k[pp] = *(const uint4*)(p.k + key * tok_stride + head_off + (tid & 15) * 8);
-  }
-  const int kq = tid >> 5, dc = tid & 31;
-#pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int key = key0 + kq * 4 + b;
-    r.v[b] = make_uint2(0, 0);
-    if (key < p.total_kv) r.v[b] = *(const uint2*)(p.v + key * tok_stride + head_off + dc * 4);
-  }
+// Value of lane ^ 32 (v_permlane32_swap: no LDS round trip).
+__device__ __forceinline__ float xor32(float x) {
+  const unsigned u = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
 }
 
-// Register -> LDS. K keeps its [key][d] layout. V is transposed: physical row
-// rho = (d % 4) * 32 + d / 4 holds channel d, and inside every block of 16 keys the key
-// (a*8 + g*4 + b) sits at slot (g*8 + a*4 + b), which is the order in which the
-// accumulator of S^T hands the probabilities to the second product.
-__device__ __forceinline__ void store_tile(char* kbuf, char* vtbuf, int tid, const TileRegs& r) {
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Global -> register staging of half a KV tile (64 keys), held while the current tile is
+// computed. Scalars, not arrays: keeps them out of scratch.
+struct HalfRegs {
+  uint4 k0, k1;          // 2 x 8 bf16 of K
+  uint2 v0, v1, v2, v3;  // 4 keys x 4 bf16 of V
+  int32_t pos;           // kv_pos of key `tid` of the half (first wavefront only)
+};
+
+// Per-thread element offsets of its loads inside a half tile; the base is wave-uniform.
+struct HalfOffsets {
+  uint32_t k[2];
+  uint32_t v[4];
+};
+
+__device__ __forceinline__ HalfOffsets half_offsets(const Params& p, int kvh, int tid) {
+  HalfOffsets o;
+  const uint32_t tok_stride = (uint32_t)p.n_kv_heads * D;
+  const uint32_t head_off = (uint32_t)kvh * D;
 #pragma unroll
   for (int pp = 0; pp < 2; ++pp)
-    *(uint4*)(kbuf + (pp * 32 + (tid >> 4)) * K_STRIDE + (tid & 15) * 16) = r.k[pp];
+    o.k[pp] = (pp * 32 + (tid >> 4)) * tok_stride + head_off + (tid & 15) * 8;
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+    o.v[b] = ((tid >> 5) * 4 + b) * tok_stride + head_off + (tid & 31) * 4;
+  return o;
+}
+
+__device__ __forceinline__ void load_half(const Params& p, const HalfOffsets& off, int kvh,
+                                          int key0, int tid, HalfRegs& r) {
+  const int64_t tok_stride = (int64_t)p.n_kv_heads * D;
+  if (key0 + SUB <= p.total_kv) {  // whole half inside the shard (uniform branch)
+    const bf16_t* kt = p.k + key0 * tok_stride;
+    const bf16_t* vt = p.v + key0 * tok_stride;
+    r.k0 = *(const uint4*)(kt + off.k[0]);
+    r.k1 = *(const uint4*)(kt + off.k[1]);
+    r.v0 = *(const uint2*)(vt + off.v[0]);
+    r.v1 = *(const uint2*)(vt + off.v[1]);
+    r.v2 = *(const uint2*)(vt + off.v[2]);
+    r.v3 = *(const uint2*)(vt + off.v[3]);
+    if (tid < SUB) r.pos = p.kv_pos[key0 + tid];
+    return;
+  }
+  // Tail: rows past the end of the shard are clamped to the last row. Their scores are
+  // masked (the tail tile always takes the mask path, and their position is the pad
+  // value) and their finite V rows meet P = 0.
+  const int last = p.total_kv - 1;
+  const int64_t head_off = (int64_t)kvh * D;
+  auto krow = [&](int pp) {
+    const int key = min(key0 + pp * 32 + (tid >> 4), last);
+    return *(const uint4*)(p.k + key * tok_stride + head_off + (tid & 15) * 8);
+  };
+  auto vrow = [&](int b) {
+    const int key = min(key0 + (tid >> 5) * 4 + b, last);
+    return *(const uint2*)(p.v + key * tok_stride + head_off + (tid & 31) * 4);
+  };
+  r.k0 = krow(0); r.k1 = krow(1);
+  r.v0 = vrow(0); r.v1 = vrow(1); r.v2 = vrow(2); r.v3 = vrow(3);
+  if (tid < SUB) r.pos = key0 + tid <= last ? p.kv_pos[key0 + tid] : CP_POS_PAD_KV;
+}
+
+// Register -> LDS for half `h` of a tile buffer. K keeps its [key][d] layout. V is
+// transposed: physical row rho = (d % 4) * 32 + d / 4 holds channel d, and inside every
+// block of 16 keys the key (a*8 + g*4 + b) sits at slot (g*8 + a*4 + b), which is the order
+// in which the accumulator of S^T hands the probabilities to the second product.
+__device__ __forceinline__ void store_half(char* kbuf, char* vtbuf, int32_t* posbuf, int h,
+                                           int tid, const HalfRegs& r) {
+  if (tid < SUB) posbuf[h * SUB + tid] = r.pos;
+  char* kh = kbuf + h * SUB * K_STRIDE;
+  *(uint4*)(kh + (tid >> 4) * K_STRIDE + (tid & 15) * 16) = r.k0;
+  *(uint4*)(kh + (32 + (tid >> 4)) * K_STRIDE + (tid & 15) * 16) = r.k1;
   const int kq = tid >> 5, dc = tid & 31;
   const int blk = kq >> 2, a = (kq & 3) >> 1, g = kq & 1;
-  const int slot0 = blk * 16 + g * 8 + a * 4;
-  const uint32_t x0 = r.v[0].x, x1 = r.v[1].x, x2 = r.v[2].x, x3 = r.v[3].x;
-  const uint32_t y0 = r.v[0].y, y1 = r.v[1].y, y2 = r.v[2].y, y3 = r.v[3].y;
+  const int slot0 = h * SUB + blk * 16 + g * 8 + a * 4;
+  const uint32_t x0 = r.v0.x, x1 = r.v1.x, x2 = r.v2.x, x3 = r.v3.x;
+  const uint32_t y0 = r.v0.y, y1 = r.v1.y, y2 = r.v2.y, y3 = r.v3.y;
   uint2 t[4];
   t[0] = make_uint2((x0 & 0xffffu) | (x1 << 16), (x2 & 0xffffu) | (x3 << 16));
   t[1] = make_uint2((x0 >> 16) | (x1 & 0xffff0000u), (x2 >> 16) | (x3 & 0xffff0000u));
@@ -133,11 +205,16 @@ __device__ __forceinline__ void store_tile(char* kbuf, char* vtbuf, int tid, con
 }
 
 template <typename TO>
-__global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(Params p) {
+__global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
+    Params p, const int2* __restrict__ tile_bounds) {
+  // tile_bounds is a separate read-only, non-aliased argument so that it is fetched
+  // without touching the counters the tile prefetch depends on.
   extern __shared__ __align__(16) char smem[];
   char* const kbuf0 = smem;
-  char* const vtbuf0 = smem + 2 * K_BYTES;
-  int* const wg_minmax = (int*)(smem + 2 * K_BYTES + 2 * VT_BYTES);
+  char* const vtbuf0 = smem + OFF_VT;
+  int32_t* const posbuf0 = (int32_t*)(smem + OFF_POS);
+  int* const wg_scratch = (int*)(smem + OFF_SCRATCH);
+  int4* const live = (int4*)(smem + OFF_LIVE);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -169,24 +246,17 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(Params p) {
     w_qmin = min(w_qmin, __shfl_xor(w_qmin, o, 64));
     w_qmax = max(w_qmax, __shfl_xor(w_qmax, o, 64));
   }
-  if (lane == 0) {
-    wg_minmax[wave * 2] = w_qmin;
-    wg_minmax[wave * 2 + 1] = w_qmax;
-  }
+  if (lane == 0) wg_scratch[wave] = w_qmax;
   __syncthreads();
   int wg_qmax = INT32_MIN;
 #pragma unroll
-  for (int w = 0; w < NWAVE; ++w) wg_qmax = max(wg_qmax, wg_minmax[w * 2 + 1]);
+  for (int w = 0; w < NWAVE; ++w) wg_qmax = max(wg_qmax, wg_scratch[w]);
+  // wave-uniform by construction; say so, so that control flow stays on the scalar unit
+  wg_qmax = __builtin_amdgcn_readfirstlane(wg_qmax);
+  w_qmin = __builtin_amdgcn_readfirstlane(w_qmin);
+  w_qmax = __builtin_amdgcn_readfirstlane(w_qmax);
 
-  // ---- KV tile range of this split ----
-  const int t_begin = split * p.tiles_per_split;
-  const int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
-  auto next_live = [&](int t) {
-    while (t < t_end && p.bounds[t].x > wg_qmax) ++t;  // smallest key position beyond every query
-    return t;
-  };
-
-  float m_run = -INFINITY;  // running max of scaled scores (log2 domain)
+  float m_run = -INFINITY;  // reference max of scaled scores (log2 domain)
   float l_run = 0.f;        // running denominator over this lane's half of the keys
   floatx16_t o_acc[4];
 #pragma unroll
@@ -194,91 +264,209 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(Params p) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
 
-  TileRegs regs;
-  int t = next_live(t_begin);
-  int buf = 0;
-  if (t < t_end) {
-    load_tile(p, kvh, t, tid, regs);
-    store_tile(kbuf0, vtbuf0, tid, regs);
-  }
-  __syncthreads();
+  HalfRegs regs;
+  const HalfOffsets hoff = half_offsets(p, kvh, tid);
+  const int k_off = n * K_STRIDE + g * 16;   // this lane's A-operand row of K
+  const int v_off = n * VT_STRIDE + g * 16;  // and of V^T
 
-  while (t < t_end) {
-    const int tn = next_live(t + 1);
-    if (tn < t_end) load_tile(p, kvh, tn, tid, regs);
-
-    const int2 bnd = p.bounds[t];
-    const bool tail = (t + 1) * BN > p.total_kv;
-    if (bnd.x <= w_qmax) {  // otherwise every key of the tile is beyond this wavefront's queries
-      const char* kb = kbuf0 + buf * K_BYTES;
-      const char* vb = vtbuf0 + buf * VT_BYTES;
-
-      // S^T = K Q^T : two blocks of 32 keys x 32 queries
-      floatx16_t s[2];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) s[0][i] = s[1][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8_t a0 = *(const bf16x8_t*)(kb + n * K_STRIDE + ks * 32 + g * 16);
-        const bf16x8_t a1 = *(const bf16x8_t*)(kb + (32 + n) * K_STRIDE + ks * 32 + g * 16);
-        s[0] = mfma32(a0, qf[ks], s[0]);
-        s[1] = mfma32(a1, qf[ks], s[1]);
+  // ---- KV tile range of this split, walked in chunks of at most MAX_LIVE tiles ----
+  const int t_begin = split * p.tiles_per_split;
+  const int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
+  for (int c0 = t_begin; c0 < t_end; c0 += MAX_LIVE) {
+    // Compact the tiles some query of the workgroup can see (smallest key position not
+    // beyond the largest query position) into an ascending list in LDS: (tile, min, max).
+    __syncthreads();  // previous chunk (list, tile buffers) fully consumed
+    {
+      const int t = c0 + wave * 64 + lane;
+      int2 b = make_int2(0, 0);
+      bool lv = false;
+      if (t < t_end) {
+        b = tile_bounds[t];
+        lv = b.x <= wg_qmax;
       }
-
-      // causal mask, only where a key position can exceed a query position
-      if (bnd.y > w_qmin || tail) {
+      const uint64_t mask = __builtin_amdgcn_ballot_w64(lv);
+      if (lane == 0) wg_scratch[wave] = __builtin_popcountll(mask);
+      __syncthreads();
+      int base = 0, total = 0;
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = t * BN + kb2 * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-            const int32_t kp = key < p.total_kv ? p.kv_pos[key] : CP_POS_PAD_KV;
-            if (kp > qp) s[kb2][i] = -INFINITY;
-          }
+      for (int w = 0; w < NWAVE; ++w) {
+        const int c = wg_scratch[w];
+        if (w < wave) base += c;
+        total += c;
       }
-
-      // online softmax in the log2 domain
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb2][i]);
-      mx = fmaxf(mx, xor32(mx));
-      const float m_new = fmaxf(m_run, mx * p.scale_log2);
-      const float m_use = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-      float lsum = 0.f;
-      bf16x8_t pb[4];
-#pragma unroll
-      for (int kb2 = 0; kb2 < 2; ++kb2)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const float e = __builtin_amdgcn_exp2f(fmaf(s[kb2][i], p.scale_log2, -m_use));
-          lsum += e;
-          pb[kb2 * 2 + (i >> 3)][i & 7] = static_cast<bf16_t>(e);
-        }
-      l_run = fmaf(l_run, alpha, lsum);
-      m_run = m_new;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
-
-      // O^T += V^T P^T : 4 blocks of 32 channels, 4 steps of 16 keys
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const bf16x8_t a = *(const bf16x8_t*)(vb + (db * 32 + n) * VT_STRIDE + kk * 32 + g * 16);
-          o_acc[db] = mfma32(a, pb[kk], o_acc[db]);
-        }
+      if (lv)
+        live[base + __builtin_popcountll(mask & ((1ull << lane) - 1ull))] =
+            make_int4(t, b.x, b.y, 0);
+      if (tid == 0) wg_scratch[NWAVE] = total;
     }
-
-    if (tn < t_end)
-      store_tile(kbuf0 + (buf ^ 1) * K_BYTES, vtbuf0 + (buf ^ 1) * VT_BYTES, tid, regs);
     __syncthreads();
-    t = tn;
-    buf ^= 1;
+    const int n_live = __builtin_amdgcn_readfirstlane(wg_scratch[NWAVE]);
+    if (n_live == 0) continue;
+
+    // prologue: first live tile into buffer 0
+    {
+      const int key0 = __builtin_amdgcn_readfirstlane(live[0].x) * TILE;
+      load_half(p, hoff, kvh, key0, tid, regs);
+      store_half(kbuf0, vtbuf0, posbuf0, 0, tid, regs);
+      if (key0 + SUB < p.total_kv) {
+        load_half(p, hoff, kvh, key0 + SUB, tid, regs);
+        store_half(kbuf0, vtbuf0, posbuf0, 1, tid, regs);
+      }
+    }
+    // Every global load so far (the Q fragments among them) has landed before the loop, so
+    // the only loads in flight inside it are the prefetch of the next tile.
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+
+    for (int it = 0; it < n_live; ++it) {
+      const int4 e = live[it];
+      const int tile = __builtin_amdgcn_readfirstlane(e.x);
+      const int bmin = __builtin_amdgcn_readfirstlane(e.y);
+      const int bmax = __builtin_amdgcn_readfirstlane(e.z);
+      const int buf = it & 1;
+      const bool has_next = it + 1 < n_live;
+      const int next_key0 =
+          has_next ? __builtin_amdgcn_readfirstlane(live[it + 1].x) * TILE : 0;
+      char* const nk = kbuf0 + (buf ^ 1) * K_BYTES;
+      char* const nv = vtbuf0 + (buf ^ 1) * VT_BYTES;
+      int32_t* const np = posbuf0 + (buf ^ 1) * TILE;
+      // a tile whose second half starts past the end of the shard has only one half
+      const bool next_two = has_next && next_key0 + SUB < p.total_kv;
+      const bool two = tile * TILE + SUB < p.total_kv;
+      // every key of the tile beyond this wavefront's queries: nothing to compute here
+      const bool wave_live = bmin <= w_qmax;
+      const bool need_mask = bmax > w_qmin || (tile + 1) * TILE > p.total_kv;
+
+      if (has_next) load_half(p, hoff, kvh, next_key0, tid, regs);
+
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        if (h == 1 && !two) break;
+        floatx16_t s[2];
+        bf16x8_t pb[4];
+        if (wave_live) {
+          const char* kb = kbuf0 + buf * K_BYTES + h * SUB * K_STRIDE + k_off;
+          // S^T = K Q^T : two blocks of 32 keys x 32 queries. A fragments are requested
+          // kReadAhead reads ahead of the MFMA that consumes them; the scheduling barriers
+          // pin that order (the default schedule reads each fragment right before its use).
+#pragma unroll
+          for (int i = 0; i < 16; ++i) s[0][i] = s[1][i] = 0.f;
+          bf16x8_t ka[16];
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) {
+            ka[2 * ks] = *(const bf16x8_t*)(kb + ks * 32);
+            ka[2 * ks + 1] = *(const bf16x8_t*)(kb + 32 * K_STRIDE + ks * 32);
+          }
+#pragma unroll
+          for (int ks = 0; ks < 8; ++ks) {
+            s[0] = mfma32(ka[2 * ks], qf[ks], s[0]);
+            s[1] = mfma32(ka[2 * ks + 1], qf[ks], s[1]);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x100, kReadAhead, 0);
+#pragma unroll
+          for (int i = 0; i < 16 - kReadAhead; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, kReadAhead, 0);
+
+          // causal mask, only where a key position can exceed a query position
+          if (need_mask) {
+            const int32_t* pb32 = posbuf0 + buf * TILE + h * SUB + g * 4;
+#pragma unroll
+            for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                const int4 kp = *(const int4*)(pb32 + kb2 * 32 + q4 * 8);  // 4 consecutive keys
+                if (kp.x > qp) s[kb2][q4 * 4 + 0] = -INFINITY;
+                if (kp.y > qp) s[kb2][q4 * 4 + 1] = -INFINITY;
+                if (kp.z > qp) s[kb2][q4 * 4 + 2] = -INFINITY;
+                if (kp.w > qp) s[kb2][q4 * 4 + 3] = -INFINITY;
+              }
+          }
+
+          // Online softmax in the log2 domain. The reference maximum m_run is only raised
+          // (and O, l rescaled) when some row's step maximum exceeds it by more than
+          // kRescaleSlack, so exponentials stay below 2^kRescaleSlack and the 64-register
+          // rescale of O is skipped on almost every step; the result is unchanged because
+          // numerator and denominator share the reference.
+          float mx0 = fmaxf(s[0][0], s[1][0]), mx1 = fmaxf(s[0][1], s[1][1]);
+#pragma unroll
+          for (int i = 2; i < 16; i += 2) {
+            mx0 = fmaxf(fmaxf(mx0, s[0][i]), s[1][i]);
+            mx1 = fmaxf(fmaxf(mx1, s[0][i + 1]), s[1][i + 1]);
+          }
+          float mx = fmaxf(mx0, mx1);
+          mx = fmaxf(mx, xor32(mx));
+          const float m_step = mx * p.scale_log2;
+          const bool raise = m_step > m_run + kRescaleSlack;  // true on the first live step
+          if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            const float m_new = fmaxf(m_run, m_step);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
+            l_run *= alpha;
+            m_run = m_new;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+              for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
+          }
+          const float m_use = m_run == -INFINITY ? 0.f : m_run;
+          // The denominator sums the unrounded exponentials: LSE must be good to 1e-3 even
+          // on rows with a handful of keys, which bf16 rounding of P would not give.
+          float lsum[2] = {0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) {
+            const int kb2 = kk >> 1, i0 = (kk & 1) * 8;
+#pragma unroll
+            for (int jj = 0; jj < 8; jj += 2) {
+              const float e0 = __builtin_amdgcn_exp2f(fmaf(s[kb2][i0 + jj], p.scale_log2, -m_use));
+              const float e1 =
+                  __builtin_amdgcn_exp2f(fmaf(s[kb2][i0 + jj + 1], p.scale_log2, -m_use));
+              lsum[(jj >> 1) & 1] += e0 + e1;
+              pb[kk][jj] = static_cast<bf16_t>(e0);
+              pb[kk][jj + 1] = static_cast<bf16_t>(e1);
+            }
+          }
+          l_run += lsum[0] + lsum[1];
+        }
+
+        // The LDS pipe is idle here: park the prefetched half of the next tile in the other
+        // buffer (nobody reads it before the barrier) and fetch the following half.
+        if (h == 0) {
+          if (has_next) {
+            store_half(nk, nv, np, 0, tid, regs);
+            if (next_two) load_half(p, hoff, kvh, next_key0 + SUB, tid, regs);
+          }
+        } else {
+          if (next_two) store_half(nk, nv, np, 1, tid, regs);
+        }
+
+        if (wave_live) {
+          // O^T += V^T P^T : 4 blocks of 32 channels, 4 steps of 16 keys
+          const char* vb = vtbuf0 + buf * VT_BYTES + h * SUB * 2 + v_off;
+          bf16x8_t va[16];
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+              va[kk * 4 + db] = *(const bf16x8_t*)(vb + db * 32 * VT_STRIDE + kk * 32);
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) o_acc[db] = mfma32(va[kk * 4 + db], pb[kk], o_acc[db]);
+          __builtin_amdgcn_sched_group_barrier(0x100, kReadAhead, 0);
+#pragma unroll
+          for (int i = 0; i < 16 - kReadAhead; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, kReadAhead, 0);
+        }
+      }
+      // single-half current tile: the second half of the next tile is still in registers
+      if (!two && next_two) store_half(nk, nv, np, 1, tid, regs);
+      __syncthreads();
+    }
   }
 
   // ---- epilogue ----
@@ -286,32 +474,50 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(Params p) {
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   const float lse_val =
       l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-  if (!row_ok) return;
-  if (p.n_splits == 1) {
-    TO* o = (TO*)p.out + row_lin * D;
+  const bool direct = p.n_splits == 1;
+  float* const lse_dst = direct ? p.lse : p.part_lse + (int64_t)split * p.rows_all_heads;
+  if (row_ok && g == 0) lse_dst[row_lin] = lse_val;
+
+  // Transpose through LDS (tile buffers are dead after the last barrier; each wavefront
+  // uses a private region): accumulator (db, i) of lane (n, g) is channel
+  // d = 4 * ((i / 4) * 8 + g * 4 + i % 4) + db of row n.
+  char* const stage = smem + wave * 32 * OUT_STRIDE;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int d0 = 4 * ((i >> 2) * 8 + g * 4 + (i & 3));  // accumulator row m holds d = 4m + db
-      if constexpr (sizeof(TO) == 4) {
-        floatx4_t w = {o_acc[0][i] * inv, o_acc[1][i] * inv, o_acc[2][i] * inv, o_acc[3][i] * inv};
-        *(floatx4_t*)((float*)o + d0) = w;
-      } else {
-        bf16x4_t w;
+  for (int i = 0; i < 16; ++i) {
+    const int d0 = 4 * ((i >> 2) * 8 + g * 4 + (i & 3));
+    floatx4_t w = {o_acc[0][i] * inv, o_acc[1][i] * inv, o_acc[2][i] * inv, o_acc[3][i] * inv};
+    *(floatx4_t*)(stage + n * OUT_STRIDE + d0 * 4) = w;
+  }
+  wave_lds_fence();
+  const int64_t r0 = (int64_t)row_block * BM + wave * 32;
+  if (direct && sizeof(TO) == 2) {
+    // 4 rows per pass: 16 lanes x 8 channels each
+    bf16_t* const o = (bf16_t*)p.out;
 #pragma unroll
-        for (int db = 0; db < 4; ++db) w[db] = static_cast<bf16_t>(o_acc[db][i] * inv);
-        *(bf16x4_t*)((bf16_t*)o + d0) = w;
+    for (int pass = 0; pass < 8; ++pass) {
+      const int rr = pass * 4 + (lane >> 4), c = (lane & 15) * 8;
+      const int64_t rl = __shfl(row_lin, rr, 64);
+      const floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      const floatx4_t b = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4 + 16);
+      bf16x8_t w;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        w[x] = static_cast<bf16_t>(a[x]);
+        w[4 + x] = static_cast<bf16_t>(b[x]);
       }
+      if (r0 + rr < p.rows) *(bf16x8_t*)(o + rl * D + c) = w;
     }
-    if (g == 0) p.lse[row_lin] = lse_val;
   } else {
-    float* o = p.part_out + ((int64_t)split * p.rows_all_heads + row_lin) * D;
+    // 2 rows per pass: 32 lanes x 4 channels each
+    float* const o =
+        direct ? (float*)p.out : p.part_out + (int64_t)split * p.rows_all_heads * D;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int d0 = 4 * ((i >> 2) * 8 + g * 4 + (i & 3));
-      floatx4_t w = {o_acc[0][i] * inv, o_acc[1][i] * inv, o_acc[2][i] * inv, o_acc[3][i] * inv};
-      *(floatx4_t*)(o + d0) = w;
+    for (int pass = 0; pass < 16; ++pass) {
+      const int rr = pass * 2 + (lane >> 5), c = (lane & 31) * 4;
+      const int64_t rl = __shfl(row_lin, rr, 64);
+      const floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      if (r0 + rr < p.rows) *(floatx4_t*)(o + rl * D + c) = a;
     }
-    if (g == 0) p.part_lse[(int64_t)split * p.rows_all_heads + row_lin] = lse_val;
   }
 }
 
@@ -326,14 +532,14 @@ Plan make_plan(const cp_shape& s) {
   Plan pl;
   const int group = s.n_q_heads / s.n_kv_heads;
   const int64_t rows = s.total_q * group;
-  pl.n_tiles = (int)((s.total_kv + BN - 1) / BN);
+  pl.n_tiles = (int)((s.total_kv + TILE - 1) / TILE);
   pl.n_row_blocks = (int)((rows + BM - 1) / BM);
   // Split the KV axis when the row blocks alone cannot occupy the 256 CUs. Every split
-  // costs one fp32 partial of the output, so keep at least 8 tiles (512 keys) per split.
+  // costs one fp32 partial of the output, so keep at least 4 tiles (512 keys) per split.
   const int64_t wgs = (int64_t)pl.n_row_blocks * s.n_kv_heads;
   int splits = 1;
-  if (wgs > 0 && wgs < 128 && pl.n_tiles >= 16) {
-    splits = (int)std::min<int64_t>((256 + wgs - 1) / wgs, pl.n_tiles / 8);
+  if (wgs > 0 && wgs < 128 && pl.n_tiles >= 8) {
+    splits = (int)std::min<int64_t>((256 + wgs - 1) / wgs, pl.n_tiles / 4);
     splits = std::max(1, std::min(splits, CP_MAX_PARTS));
   }
   pl.tiles_per_split = pl.n_tiles > 0 ? (pl.n_tiles + splits - 1) / splits : 1;
@@ -353,12 +559,12 @@ size_t prefill_mfma_workspace_bytes(const cp_shape& s) {
 }
 
 size_t kv_tile_bounds_bytes(int64_t total_kv) {
-  return round256((size_t)std::max<int64_t>((total_kv + BN - 1) / BN, 1) * sizeof(int2));
+  return round256((size_t)std::max<int64_t>((total_kv + TILE - 1) / TILE, 1) * sizeof(int2));
 }
 
 int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_out,
                           hipStream_t stream) {
-  const int n_tiles = (int)((total_kv + BN - 1) / BN);
+  const int n_tiles = (int)((total_kv + TILE - 1) / TILE);
   if (n_tiles == 0) return CP_OK;
   hipLaunchKernelGGL(kv_tile_bounds_kernel, dim3((n_tiles + 3) / 4), dim3(256), 0, stream, kv_pos,
                      (int32_t)total_kv, n_tiles, (int2*)bounds_out);
@@ -402,7 +608,7 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                           SMEM_BYTES) != hipSuccess)
     return CP_ERR_LAUNCH;
-  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), SMEM_BYTES, stream, p);
+  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), SMEM_BYTES, stream, p, p.bounds);
   if (check_launch() != CP_OK) return CP_ERR_LAUNCH;
 
   if (pl.n_splits > 1)

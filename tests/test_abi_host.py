@@ -135,9 +135,9 @@ def test_merge_validates_before_launching(lib):
 
 
 def test_workspace_sizes(lib):
-    # long query shard: only the per-tile position bounds (8 bytes per 64 keys)
+    # long query shard: only the per-tile position bounds (8 bytes per 128 keys)
     big = _shape(total_q=8192, total_kv=8192)
-    assert B.cp_workspace_bytes(big, B.CP_WS_PARTIAL) == 128 * 8
+    assert B.cp_workspace_bytes(big, B.CP_WS_PARTIAL) == 64 * 8
     # short query shard: split over KV, fp32 partial O and LSE per split
     small = _shape(total_q=64, total_kv=8256)
     n = B.cp_workspace_bytes(small, B.CP_WS_PARTIAL)
