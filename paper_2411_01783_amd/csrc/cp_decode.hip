@@ -6,11 +6,12 @@
 // of v_mfma_f32_16x16x32_bf16 and the keys as the M side (S^T = K Q^T, then
 // O^T += V^T P^T), which keeps the softmax statistics per lane.
 //
-// grid = (n_splits, n_queries, n_kv_heads). A workgroup of 4 wavefronts takes
-// one contiguous slice of the query's KV segment; its wavefronts take 32-key
-// tiles round-robin, each staging its tile through a private LDS region
-// (K swizzled, V transposed on the way in; coalesced 256-byte row reads from
-// HBM, the next tile prefetched into registers while the current one is used).
+// grid = (n_splits, n_queries, n_kv_heads), sized so that all workgroups are
+// resident at once (two workgroups of 4 wavefronts per CU). A workgroup takes one
+// contiguous slice of the query's KV segment; its wavefronts take 32-key tiles
+// round-robin, each staging its tile through a private LDS region (K swizzled, V
+// transposed on the way in; every HBM read is a full 256-byte row per 16 lanes,
+// the next tile is prefetched into registers while the current one is used).
 // The four wavefront results are combined in LDS and written as one fp32
 // partial (O, LSE) per split; Equation 4 over the splits finishes the call.
 #include "cp_common.h"
@@ -26,8 +27,9 @@ constexpr int K_TILE_BYTES = TILE * D * 2;      // 8 KiB, rows of 256 B, 16-byte
 constexpr int VT_STRIDE = TILE * 2 + 16;        // 80 B per channel row (32 keys + pad)
 constexpr int VT_TILE_BYTES = D * VT_STRIDE;    // 10 KiB
 constexpr int WAVE_LDS = K_TILE_BYTES + VT_TILE_BYTES;
-constexpr int COMBINE_BYTES = NWAVE * (16 * D + 32) * 4;  // O^T + (m, l) per wavefront
-static_assert(NWAVE * WAVE_LDS >= COMBINE_BYTES, "combine buffer aliases the tile buffers");
+constexpr int CB_STRIDE = D + 4;                // combine buffer: one head row of O + pad (floats)
+constexpr int CB_WAVE = 16 * CB_STRIDE + 32;    // 16 heads + (m, l) per wavefront (floats)
+static_assert(NWAVE * WAVE_LDS >= NWAVE * CB_WAVE * 4, "combine buffer aliases the tile buffers");
 
 struct Params {
   const bf16_t* q;
@@ -51,61 +53,12 @@ __device__ __forceinline__ floatx4_t mfma16(bf16x8_t a, bf16x8_t b, floatx4_t c)
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
 
+// One 32-key tile in flight: 8 x 16 B of K and 8 x 16 B of V per lane (scalars, not arrays).
 struct TileRegs {
-  uint4 k[8];      // 8 x 16 B of K: row it*4 + lane/16, chunk lane%16
-  uint2 v[4][4];   // item it: key quad (lane/32 + 2*it), channels (lane%32)*4..+3, 4 keys
+  uint4 k0, k1, k2, k3, k4, k5, k6, k7;  // row it*4 + lane/16, chunk lane%16
+  uint4 v0, v1, v2, v3, v4, v5, v6, v7;  // it = 0,1: keys (lane/16 + 4*it)*4 + b, channels (lane%16)*8..+7
+  int32_t p0, p1, p2, p3, p4, p5, p6, p7;  // kv_pos of keys kb*16 + (lane/16)*4 + i (this lane's scores)
 };
-
-__device__ __forceinline__ void load_tile(const Params& p, int kvh, int64_t key0, int n_valid,
-                                          int lane, TileRegs& r) {
-  const int64_t tok_stride = (int64_t)p.n_kv_heads * D;
-  const bf16_t* kbase = p.k + key0 * tok_stride + (int64_t)kvh * D;
-  const bf16_t* vbase = p.v + key0 * tok_stride + (int64_t)kvh * D;
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int key = it * 4 + (lane >> 4);
-    r.k[it] = make_uint4(0, 0, 0, 0);
-    if (key < n_valid) r.k[it] = *(const uint4*)(kbase + key * tok_stride + (lane & 15) * 8);
-  }
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int kq = (lane >> 5) + 2 * it;
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int key = kq * 4 + b;
-      r.v[it][b] = make_uint2(0, 0);
-      if (key < n_valid) r.v[it][b] = *(const uint2*)(vbase + key * tok_stride + (lane & 31) * 4);
-    }
-  }
-}
-
-// K: chunk c of row `key` goes to chunk position c ^ (key & 15) (conflict-free b128 reads by
-// 16 lanes that hold 16 different keys). V: transposed; physical row (d % 4) * 32 + d / 4
-// holds channel d; key (a*16 + kg*4 + b) of the tile sits at slot kg*8 + a*4 + b, the order
-// in which two 16-key score blocks feed the B operand of the second product.
-__device__ __forceinline__ void store_tile(char* kbuf, char* vtbuf, int lane, const TileRegs& r) {
-#pragma unroll
-  for (int it = 0; it < 8; ++it) {
-    const int key = it * 4 + (lane >> 4);
-    *(uint4*)(kbuf + key * 256 + (((lane & 15) ^ (key & 15)) << 4)) = r.k[it];
-  }
-  const int dc = lane & 31;
-#pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int kq = (lane >> 5) + 2 * it;           // keys kq*4 .. kq*4+3
-    const int slot0 = (kq & 3) * 8 + (kq >> 2) * 4;
-    const uint32_t x0 = r.v[it][0].x, x1 = r.v[it][1].x, x2 = r.v[it][2].x, x3 = r.v[it][3].x;
-    const uint32_t y0 = r.v[it][0].y, y1 = r.v[it][1].y, y2 = r.v[it][2].y, y3 = r.v[it][3].y;
-    uint2 t[4];
-    t[0] = make_uint2((x0 & 0xffffu) | (x1 << 16), (x2 & 0xffffu) | (x3 << 16));
-    t[1] = make_uint2((x0 >> 16) | (x1 & 0xffff0000u), (x2 >> 16) | (x3 & 0xffff0000u));
-    t[2] = make_uint2((y0 & 0xffffu) | (y1 << 16), (y2 & 0xffffu) | (y3 << 16));
-    t[3] = make_uint2((y0 >> 16) | (y1 & 0xffff0000u), (y2 >> 16) | (y3 & 0xffff0000u));
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *(uint2*)(vtbuf + (i * 32 + dc) * VT_STRIDE + slot0 * 2) = t[i];
-  }
-}
 
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -113,7 +66,7 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
+__global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
@@ -123,16 +76,11 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
   char* const kbuf = smem + wave * WAVE_LDS;
   char* const vtbuf = kbuf + K_TILE_BYTES;
 
+  // segment of this query's sequence, this workgroup's slice of it
   const int b = p.bid[qi];
-  const int64_t seg0 = p.cu_kv[b], seg1 = p.cu_kv[b + 1];
-  const int64_t len = seg1 - seg0;
-  int64_t chunk = (len + p.n_splits - 1) / p.n_splits;
-  chunk = (chunk + TILE - 1) / TILE * TILE;
-  const int64_t c0 = seg0 + (int64_t)split * chunk;
-  const int64_t c1 = min(seg1, c0 + chunk);
   const int32_t qp = p.q_pos[qi];
-
-  // Q^T fragments: lane (hd, kg) holds channels kg*32 + ks*8 .. +7 of head hd
+  // Q^T fragments (independent of the segment lookup): lane (hd, kg) holds channels
+  // kg*32 + ks*8 .. +7 of head hd
   bf16x8_t qf[4];
   const bool head_ok = hd < p.group;
 #pragma unroll
@@ -143,23 +91,121 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
                           ks * 8);
     qf[ks] = __builtin_bit_cast(bf16x8_t, t);
   }
+  const int64_t seg0 = p.cu_kv[b], seg1 = p.cu_kv[b + 1];
+  const int64_t len = seg1 - seg0;
+  int64_t chunk = (len + p.n_splits - 1) / p.n_splits;
+  chunk = (chunk + TILE - 1) / TILE * TILE;
+  const int64_t c0 = seg0 + (int64_t)split * chunk;
+  const int64_t c1 = min(seg1, c0 + chunk);
+
+  // per-lane element offsets inside a tile (the tile base is wave-uniform)
+  const uint32_t tok_stride = (uint32_t)p.n_kv_heads * D;
+  const uint32_t koff = (uint32_t)(lane >> 4) * tok_stride + kvh * D + (lane & 15) * 8;
+  const uint32_t voff = (uint32_t)(lane >> 4) * 4 * tok_stride + kvh * D + (lane & 15) * 8;
 
   float m_run = -INFINITY, l_run = 0.f;
   floatx4_t o_acc[8];
 #pragma unroll
   for (int db = 0; db < 8; ++db) o_acc[db] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  TileRegs regs;
+  TileRegs r;
+  // Rows past the end of the slice are clamped to its last row: their scores are masked
+  // (position = pad) and their finite V rows meet P = 0.
+  auto load_tile = [&](int64_t key0) {
+    const int n_valid = (int)min<int64_t>(TILE, c1 - key0);
+    const bf16_t* kt = p.k + key0 * tok_stride;
+    const bf16_t* vt = p.v + key0 * tok_stride;
+    {
+      const int32_t* pp = p.kv_pos + key0;
+      const int last = n_valid - 1, q4 = (lane >> 4) * 4;
+      auto pos = [&](int kk) { return kk <= last ? pp[kk] : CP_POS_PAD_KV; };
+      r.p0 = pos(q4); r.p1 = pos(q4 + 1); r.p2 = pos(q4 + 2); r.p3 = pos(q4 + 3);
+      r.p4 = pos(16 + q4); r.p5 = pos(17 + q4); r.p6 = pos(18 + q4); r.p7 = pos(19 + q4);
+    }
+    if (n_valid == TILE) {
+      r.k0 = *(const uint4*)(kt + koff);
+      r.k1 = *(const uint4*)(kt + koff + 4 * tok_stride);
+      r.k2 = *(const uint4*)(kt + koff + 8 * tok_stride);
+      r.k3 = *(const uint4*)(kt + koff + 12 * tok_stride);
+      r.k4 = *(const uint4*)(kt + koff + 16 * tok_stride);
+      r.k5 = *(const uint4*)(kt + koff + 20 * tok_stride);
+      r.k6 = *(const uint4*)(kt + koff + 24 * tok_stride);
+      r.k7 = *(const uint4*)(kt + koff + 28 * tok_stride);
+      r.v0 = *(const uint4*)(vt + voff);
+      r.v1 = *(const uint4*)(vt + voff + tok_stride);
+      r.v2 = *(const uint4*)(vt + voff + 2 * tok_stride);
+      r.v3 = *(const uint4*)(vt + voff + 3 * tok_stride);
+      r.v4 = *(const uint4*)(vt + voff + 16 * tok_stride);
+      r.v5 = *(const uint4*)(vt + voff + 17 * tok_stride);
+      r.v6 = *(const uint4*)(vt + voff + 18 * tok_stride);
+      r.v7 = *(const uint4*)(vt + voff + 19 * tok_stride);
+    } else {
+      const int last = n_valid - 1;
+      const uint32_t col = kvh * D + (lane & 15) * 8;
+      auto krow = [&](int it) {
+        return *(const uint4*)(kt + (uint32_t)min(it * 4 + (lane >> 4), last) * tok_stride + col);
+      };
+      auto vrow = [&](int it, int bb) {
+        return *(const uint4*)(vt + (uint32_t)min(((lane >> 4) + 4 * it) * 4 + bb, last) * tok_stride + col);
+      };
+      r.k0 = krow(0); r.k1 = krow(1); r.k2 = krow(2); r.k3 = krow(3);
+      r.k4 = krow(4); r.k5 = krow(5); r.k6 = krow(6); r.k7 = krow(7);
+      r.v0 = vrow(0, 0); r.v1 = vrow(0, 1); r.v2 = vrow(0, 2); r.v3 = vrow(0, 3);
+      r.v4 = vrow(1, 0); r.v5 = vrow(1, 1); r.v6 = vrow(1, 2); r.v7 = vrow(1, 3);
+    }
+  };
+
+  // K: chunk c of row `key` goes to chunk position c ^ (key & 15) (conflict-free b128 reads
+  // by 16 lanes that hold 16 different keys). V: transposed; physical row (d % 8) * 16 + d / 8
+  // holds channel d; key (a*16 + kq*4 + b) of the tile sits at slot kq*8 + a*4 + b, the order
+  // in which two 16-key score blocks feed the B operand of the second product.
+  auto store_v = [&](int it, const uint4& a0, const uint4& a1, const uint4& a2, const uint4& a3) {
+    const int kq = lane >> 4;             // key quad inside the 16-key block `it`
+    const int dc = lane & 15;
+    const int slot0 = kq * 8 + it * 4;
+    const uint32_t w0[4] = {a0.x, a0.y, a0.z, a0.w}, w1[4] = {a1.x, a1.y, a1.z, a1.w};
+    const uint32_t w2[4] = {a2.x, a2.y, a2.z, a2.w}, w3[4] = {a3.x, a3.y, a3.z, a3.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {  // channel pair (2j, 2j+1) of this lane's 8 channels
+      const uint2 lo = make_uint2((w0[j] & 0xffffu) | (w1[j] << 16), (w2[j] & 0xffffu) | (w3[j] << 16));
+      const uint2 hi = make_uint2((w0[j] >> 16) | (w1[j] & 0xffff0000u),
+                                  (w2[j] >> 16) | (w3[j] & 0xffff0000u));
+      *(uint2*)(vtbuf + ((2 * j) * 16 + dc) * VT_STRIDE + slot0 * 2) = lo;
+      *(uint2*)(vtbuf + ((2 * j + 1) * 16 + dc) * VT_STRIDE + slot0 * 2) = hi;
+    }
+  };
+  auto store_tile = [&]() {
+    const int c = lane & 15, k4 = lane >> 4;
+#define CP_STORE_K(IT, REG)                                                                  \
+  *(uint4*)(kbuf + ((IT) * 4 + k4) * 256 + ((c ^ (((IT) * 4 + k4) & 15)) << 4)) = REG;
+    CP_STORE_K(0, r.k0) CP_STORE_K(1, r.k1) CP_STORE_K(2, r.k2) CP_STORE_K(3, r.k3)
+    CP_STORE_K(4, r.k4) CP_STORE_K(5, r.k5) CP_STORE_K(6, r.k6) CP_STORE_K(7, r.k7)
+#undef CP_STORE_K
+    store_v(0, r.v0, r.v1, r.v2, r.v3);
+    store_v(1, r.v4, r.v5, r.v6, r.v7);
+  };
+
   int64_t key0 = c0 + (int64_t)wave * TILE;
-  if (key0 < c1) load_tile(p, kvh, key0, (int)min<int64_t>(TILE, c1 - key0), lane, regs);
+  if (key0 < c1) load_tile(key0);
 
   while (key0 < c1) {
-    const int n_valid = (int)min<int64_t>(TILE, c1 - key0);
+    // positions of the 8 keys whose scores this lane holds (block kb, key kg*4 + i)
+    const int32_t kp[8] = {r.p0, r.p1, r.p2, r.p3, r.p4, r.p5, r.p6, r.p7};
+#ifdef DEC_NOCOMPUTE
+    {  // timing experiment: consume the registers without LDS or MFMA work
+      const uint32_t x = r.k0.x ^ r.k1.x ^ r.k2.x ^ r.k3.x ^ r.k4.x ^ r.k5.x ^ r.k6.x ^ r.k7.x ^
+                         r.v0.x ^ r.v1.x ^ r.v2.x ^ r.v3.x ^ r.v4.x ^ r.v5.x ^ r.v6.x ^ r.v7.x;
+      l_run += __builtin_bit_cast(float, x & 0x3f800000u) + (float)kp[0];
+      const int64_t kn = key0 + NWAVE * TILE;
+      if (kn < c1) load_tile(kn);
+      key0 = kn;
+      continue;
+    }
+#endif
     wave_lds_sync();  // previous tile's LDS reads are done before it is overwritten
-    store_tile(kbuf, vtbuf, lane, regs);
+    store_tile();
     const int64_t key_next = key0 + NWAVE * TILE;
-    if (key_next < c1)
-      load_tile(p, kvh, key_next, (int)min<int64_t>(TILE, c1 - key_next), lane, regs);
+    if (key_next < c1) load_tile(key_next);
     wave_lds_sync();
 
     // S^T = K Q^T for two blocks of 16 keys
@@ -176,15 +222,12 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
         s[kb] = mfma16(a, qf[ks], s[kb]);
       }
     }
-    // mask: lane (hd, kg) register i of block kb is key kb*16 + kg*4 + i
     float mx = -INFINITY;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int kk = kb * 16 + kg * 4 + i;
-        const int32_t kp = kk < n_valid ? p.kv_pos[key0 + kk] : CP_POS_PAD_KV;
-        if (kp > qp) s[kb][i] = -INFINITY;
+        if (kp[kb * 4 + i] > qp) s[kb][i] = -INFINITY;
         mx = fmaxf(mx, s[kb][i]);
       }
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -204,7 +247,7 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
       }
     l_run = fmaf(l_run, alpha, lsum);
     m_run = m_new;
-    // O^T += V^T P^T over 8 blocks of 16 channels
+    // O^T += V^T P^T over 8 blocks of 16 channels (block db holds channels hd*8 + db)
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       const bf16x8_t a = *(const bf16x8_t*)(vtbuf + (db * 16 + hd) * VT_STRIDE + kg * 16);
@@ -220,20 +263,19 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
   l_run += __shfl_xor(l_run, 32, 64);
   __syncthreads();  // all tile buffers are dead
   float* const cbuf = (float*)smem;
-  float* const my = cbuf + wave * (16 * D + 32);
-  // O^T accumulator (db, i) of lane (hd, kg) is physical V row rho = db*16 + kg*4 + i,
-  // i.e. channel d = 4 * (rho % 32) + rho / 32
+  float* const my = cbuf + wave * CB_WAVE;
+  // accumulator (db, i) of lane (hd, kg) is O^T row m = kg*4 + i of block db: channel m*8 + db
 #pragma unroll
-  for (int db = 0; db < 8; ++db)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int rho = db * 16 + kg * 4 + i;
-      const int d = 4 * (rho & 31) + (rho >> 5);
-      my[hd * D + d] = o_acc[db][i];
-    }
+  for (int i = 0; i < 4; ++i) {
+    const int d0 = (kg * 4 + i) * 8;
+    floatx4_t w0 = {o_acc[0][i], o_acc[1][i], o_acc[2][i], o_acc[3][i]};
+    floatx4_t w1 = {o_acc[4][i], o_acc[5][i], o_acc[6][i], o_acc[7][i]};
+    *(floatx4_t*)(my + hd * CB_STRIDE + d0) = w0;
+    *(floatx4_t*)(my + hd * CB_STRIDE + d0 + 4) = w1;
+  }
   if (kg == 0) {
-    my[16 * D + hd] = m_run;
-    my[16 * D + 16 + hd] = l_run;
+    my[16 * CB_STRIDE + hd] = m_run;
+    my[16 * CB_STRIDE + 16 + hd] = l_run;
   }
   __syncthreads();
   // thread -> (head = tid / 16, channels (tid % 16) * 8 .. +7)
@@ -242,8 +284,8 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
     float mw[NWAVE], lw[NWAVE], mmax = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NWAVE; ++w) {
-      mw[w] = cbuf[w * (16 * D + 32) + 16 * D + h];
-      lw[w] = cbuf[w * (16 * D + 32) + 16 * D + 16 + h];
+      mw[w] = cbuf[w * CB_WAVE + 16 * CB_STRIDE + h];
+      lw[w] = cbuf[w * CB_WAVE + 16 * CB_STRIDE + 16 + h];
       mmax = fmaxf(mmax, mw[w]);
     }
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -253,9 +295,13 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
       for (int w = 0; w < NWAVE; ++w) {
         const float f = __builtin_amdgcn_exp2f(mw[w] - mmax);
         den = fmaf(lw[w], f, den);
-        const float* src = cbuf + w * (16 * D + 32) + h * D + d0;
+        const float* src = cbuf + w * CB_WAVE + h * CB_STRIDE + d0;
+        const floatx4_t x0 = *(const floatx4_t*)src, x1 = *(const floatx4_t*)(src + 4);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) acc[c] = fmaf(src[c], f, acc[c]);
+        for (int c = 0; c < 4; ++c) {
+          acc[c] = fmaf(x0[c], f, acc[c]);
+          acc[4 + c] = fmaf(x1[c], f, acc[4 + c]);
+        }
       }
     }
     if (h < p.group) {
@@ -275,12 +321,16 @@ __global__ __launch_bounds__(NTHREADS) void decode_kernel(Params p) {
 
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// Power-of-two split count: about 512 workgroups in total (two per CU, all resident at
+// once), at least 128 keys per split on average.
 int plan_splits(const cp_shape& s) {
   const int64_t wg_per_split = std::max<int64_t>(1, s.total_q * s.n_kv_heads);
   const int64_t avg_len = s.batch > 0 ? s.total_kv / s.batch : 0;
-  int64_t splits = (768 + wg_per_split - 1) / wg_per_split;
-  splits = std::min<int64_t>(splits, (avg_len + 127) / 128);
-  return (int)std::max<int64_t>(1, std::min<int64_t>(splits, CP_MAX_PARTS));
+  int splits = 1;
+  while (splits < CP_MAX_PARTS && wg_per_split * splits * 2 <= 512 &&
+         (int64_t)splits * 2 * 128 <= avg_len)
+    splits *= 2;
+  return splits;
 }
 
 }  // namespace
@@ -300,6 +350,8 @@ int launch_decode(const cp_shape& s, float scale, const void* q, const void* k, 
   const size_t out_bytes = round256(splits * rows * D * 4);
   if (workspace_bytes < out_bytes + round256(splits * rows * 4)) return CP_ERR_WORKSPACE;
   if (s.total_q > 65535 || s.n_kv_heads > 65535) return CP_ERR_SHAPE;
+  // per-lane offsets inside a 32-key tile are kept in 32 bits
+  if ((int64_t)s.n_kv_heads * D * 64 > 0x7fffffffLL) return CP_ERR_SHAPE;
 
   Params p;
   p.q = (const bf16_t*)q; p.k = (const bf16_t*)k; p.v = (const bf16_t*)v;

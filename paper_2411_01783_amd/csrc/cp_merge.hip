@@ -75,12 +75,15 @@ __global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float*
     const int64_t row = idx / vec_per_row;
     const int col = (int)(idx - row * vec_per_row) * VEC;
 
+    // With a compile-time part count the LSE values stay in registers; with a run-time
+    // count they are read twice (a per-thread array indexed at run time would live in scratch).
     float lmax = -INFINITY;
-    float lv[NP > 0 ? NP : CP_MAX_PARTS];
+    float lv[NP > 0 ? NP : 1];
 #pragma unroll
     for (int s = 0; s < n_parts; ++s) {
-      lv[s] = STRIDED ? parts_lse[s * part_stride_rows + row] : ptrs.lse[s][row];
-      lmax = fmaxf(lmax, lv[s]);
+      const float x = STRIDED ? parts_lse[s * part_stride_rows + row] : ptrs.lse[s][row];
+      if (NP > 0) lv[NP > 0 ? s : 0] = x;
+      lmax = fmaxf(lmax, x);
     }
     float acc[VEC];
 #pragma unroll
@@ -89,15 +92,17 @@ __global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float*
     if (lmax != -INFINITY) {
 #pragma unroll
       for (int s = 0; s < n_parts; ++s) {
-        const float w = __expf(lv[s] - lmax);  // exp(-inf) = 0 for empty partials
+        const float x = NP > 0 ? lv[NP > 0 ? s : 0]
+                               : (STRIDED ? parts_lse[s * part_stride_rows + row] : ptrs.lse[s][row]);
+        const float w = __expf(x - lmax);  // exp(-inf) = 0 for empty partials
         den += w;
         if (w != 0.f) {
           const TP* p = STRIDED ? (const TP*)(parts_out + (s * part_stride_rows + row) * head_dim)
                                 : (const TP*)ptrs.out[s] + row * head_dim;
-          float x[VEC];
-          load_vec<TP, VEC>(p + col, x);
+          float x4[VEC];
+          load_vec<TP, VEC>(p + col, x4);
 #pragma unroll
-          for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, x[i], acc[i]);
+          for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, x4[i], acc[i]);
         }
       }
       const float inv = 1.f / den;
@@ -128,6 +133,8 @@ int launch_np(const MergePtrs& ptrs, const float* parts_out, const float* parts_
     case 4: CP_MERGE_LAUNCH(4); break;
     case 8: CP_MERGE_LAUNCH(8); break;
     case 16: CP_MERGE_LAUNCH(16); break;
+    case 32: if (STRIDED) { CP_MERGE_LAUNCH(32); } else { CP_MERGE_LAUNCH(0); } break;
+    case 64: if (STRIDED) { CP_MERGE_LAUNCH(64); } else { CP_MERGE_LAUNCH(0); } break;
     default: CP_MERGE_LAUNCH(0); break;
   }
 #undef CP_MERGE_LAUNCH
