@@ -73,22 +73,23 @@ def time_steps(fn, steps: int, warmup: int) -> float:
 
 
 def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
-    """HIP-event time of every partial-attention call of the given ranks' ring loops."""
+    """HIP-event time of the partial-attention launches of the given ranks' ring loops.
+
+    One event pair brackets the n back-to-back launches of a rank's loop (events between
+    the launches would add a dispatch gap to every one of them), a second pair the merge."""
     n = w.n_ranks
     ring = st["ring"]
     total_ms, total_flop, n_launch = 0.0, 0.0, 0
     merge_ms, merge_bytes = 0.0, 0.0
     ws = ring.workspace
     for kq in ranks:
-        evs = []
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
         for j in range(n):
             s = (kq - j) % n
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
             B.cp_attn_partial(st["qs"][kq], st["ks"][s], st["vs"][s], st["ps"][kq], st["ps"][s],
                               out=ring.partial_out[s], lse=ring.partial_lse[s], workspace=ws)
-            e1.record()
-            evs.append((e0, e1, s))
+        e1.record()
         m0, m1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         m0.record()
         B.cp_attn_merge([ring.partial_out[s] for s in range(n)],
@@ -96,11 +97,11 @@ def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
                         lse_out=ring.lse[kq])
         m1.record()
         torch.cuda.synchronize()
-        for e0, e1, s in evs:
-            total_ms += e0.elapsed_time(e1)
+        total_ms += e0.elapsed_time(e1)
+        for s in range(n):
             total_flop += 4.0 * w.head_dim * w.n_q_heads * visible_pairs(st["pos"][kq],
                                                                          st["pos"][s])
-            n_launch += 1
+        n_launch += n
         merge_ms += m0.elapsed_time(m1)
         rows = ring.out[kq].shape[0] * w.n_q_heads
         merge_bytes += n * rows * (w.head_dim * 4 + 4) + rows * (w.head_dim * 2 + 4)
@@ -182,6 +183,36 @@ def bench_decode(w: W.Workload, reps: int = 20):
 
 
 # ---------------------------------------------------------------------------
+# HBM traffic (hardware counters)
+# ---------------------------------------------------------------------------
+
+PROBE_COPY_BYTES = 1 << 28
+
+
+def pmc_probe(ring):
+    """The work the counter runs profile: a streaming kernel that reads and writes
+    PROBE_COPY_BYTES (the scale reference), one pass-KV ring pass, one decode pass."""
+    src = torch.ones(PROBE_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.mul(src, 2.0, out=dst)
+    torch.cuda.synchronize()
+    B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    bench_decode(W.WORKLOADS["decode_b32"], reps=1)
+    print("pmc probe done")
+
+
+def stored_traffic(kernel: str, workload: str):
+    """Bytes of HBM traffic per launch from the committed counter summary, or None."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_hbm_traffic.txt" % (kernel, workload))
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return float(line.split("=")[1])
+    return None
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -192,6 +223,9 @@ def main():
                     choices=["prefill_128k", "prefill_1m"])
     ap.add_argument("--no-aux", action="store_true", help="skip the decode measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--pmc-probe", action="store_true",
+                    help="run one ring pass, one decode pass and a plain streaming kernel of "
+                         "known size, then exit (the workload of the rocprofv3 --pmc runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the ring is simulated over virtual CP ranks on a "
@@ -206,12 +240,15 @@ def main():
     w = W.WORKLOADS[args.workload]
     st = build_prefill(w)
     ring = st["ring"]
+    if args.pmc_probe:
+        pmc_probe(ring)
+        return
     sec = time_steps(lambda: B.cp_ring_passkv(ring), args.steps, args.warmup)
     t = w.t_new
     flop_step = 4.0 * w.head_dim * w.n_q_heads * (t * (t + 1) // 2)
     tflops = flop_step / sec / 1e12
 
-    kp = kernel_pass_prefill(w, st, ranks=[0, w.n_ranks // 2, w.n_ranks - 1])
+    kp = kernel_pass_prefill(w, st, ranks=list(range(w.n_ranks)))
     achieved = kp["flop_per_launch"] / (kp["ms_per_launch"] * 1e-3) / 1e12
     result = {
         "metric": "per-rank partial-attn+merge TFLOP/s (% bf16 MFMA peak); decode HBM GB/s",
@@ -226,7 +263,8 @@ def main():
         "frac_of_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
         "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": stored_traffic("prefill_mfma_kernel", w.name),
                      "us_per_launch": round(kp["ms_per_launch"] * 1e3, 2),
                      "flop_per_launch": kp["flop_per_launch"], "launches": kp["n_launch"]},
         "aux": {"merge": {"ms": round(kp["merge_ms"], 4),
