@@ -60,6 +60,16 @@ struct TileRegs {
   int32_t p0, p1, p2, p3, p4, p5, p6, p7;  // kv_pos of keys kb*16 + (lane/16)*4 + i (this lane's scores)
 };
 
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+// K and V are read exactly once: streaming (non-temporal) loads
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+#ifdef DEC_PLAIN_LOADS
+  return *(const uint4*)p;
+#else
+  return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)p));
+#endif
+}
+
 __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -123,30 +133,30 @@ __global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
       r.p4 = pos(16 + q4); r.p5 = pos(17 + q4); r.p6 = pos(18 + q4); r.p7 = pos(19 + q4);
     }
     if (n_valid == TILE) {
-      r.k0 = *(const uint4*)(kt + koff);
-      r.k1 = *(const uint4*)(kt + koff + 4 * tok_stride);
-      r.k2 = *(const uint4*)(kt + koff + 8 * tok_stride);
-      r.k3 = *(const uint4*)(kt + koff + 12 * tok_stride);
-      r.k4 = *(const uint4*)(kt + koff + 16 * tok_stride);
-      r.k5 = *(const uint4*)(kt + koff + 20 * tok_stride);
-      r.k6 = *(const uint4*)(kt + koff + 24 * tok_stride);
-      r.k7 = *(const uint4*)(kt + koff + 28 * tok_stride);
-      r.v0 = *(const uint4*)(vt + voff);
-      r.v1 = *(const uint4*)(vt + voff + tok_stride);
-      r.v2 = *(const uint4*)(vt + voff + 2 * tok_stride);
-      r.v3 = *(const uint4*)(vt + voff + 3 * tok_stride);
-      r.v4 = *(const uint4*)(vt + voff + 16 * tok_stride);
-      r.v5 = *(const uint4*)(vt + voff + 17 * tok_stride);
-      r.v6 = *(const uint4*)(vt + voff + 18 * tok_stride);
-      r.v7 = *(const uint4*)(vt + voff + 19 * tok_stride);
+      r.k0 = load_stream16(kt + koff);
+      r.k1 = load_stream16(kt + koff + 4 * tok_stride);
+      r.k2 = load_stream16(kt + koff + 8 * tok_stride);
+      r.k3 = load_stream16(kt + koff + 12 * tok_stride);
+      r.k4 = load_stream16(kt + koff + 16 * tok_stride);
+      r.k5 = load_stream16(kt + koff + 20 * tok_stride);
+      r.k6 = load_stream16(kt + koff + 24 * tok_stride);
+      r.k7 = load_stream16(kt + koff + 28 * tok_stride);
+      r.v0 = load_stream16(vt + voff);
+      r.v1 = load_stream16(vt + voff + tok_stride);
+      r.v2 = load_stream16(vt + voff + 2 * tok_stride);
+      r.v3 = load_stream16(vt + voff + 3 * tok_stride);
+      r.v4 = load_stream16(vt + voff + 16 * tok_stride);
+      r.v5 = load_stream16(vt + voff + 17 * tok_stride);
+      r.v6 = load_stream16(vt + voff + 18 * tok_stride);
+      r.v7 = load_stream16(vt + voff + 19 * tok_stride);
     } else {
       const int last = n_valid - 1;
       const uint32_t col = kvh * D + (lane & 15) * 8;
       auto krow = [&](int it) {
-        return *(const uint4*)(kt + (uint32_t)min(it * 4 + (lane >> 4), last) * tok_stride + col);
+        return load_stream16(kt + (uint32_t)min(it * 4 + (lane >> 4), last) * tok_stride + col);
       };
       auto vrow = [&](int it, int bb) {
-        return *(const uint4*)(vt + (uint32_t)min(((lane >> 4) + 4 * it) * 4 + bb, last) * tok_stride + col);
+        return load_stream16(vt + (uint32_t)min(((lane >> 4) + 4 * it) * 4 + bb, last) * tok_stride + col);
       };
       r.k0 = krow(0); r.k1 = krow(1); r.k2 = krow(2); r.k3 = krow(3);
       r.k4 = krow(4); r.k5 = krow(5); r.k6 = krow(6); r.k7 = krow(7);
@@ -191,17 +201,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
   while (key0 < c1) {
     // positions of the 8 keys whose scores this lane holds (block kb, key kg*4 + i)
     const int32_t kp[8] = {r.p0, r.p1, r.p2, r.p3, r.p4, r.p5, r.p6, r.p7};
-#ifdef DEC_NOCOMPUTE
-    {  // timing experiment: consume the registers without LDS or MFMA work
-      const uint32_t x = r.k0.x ^ r.k1.x ^ r.k2.x ^ r.k3.x ^ r.k4.x ^ r.k5.x ^ r.k6.x ^ r.k7.x ^
-                         r.v0.x ^ r.v1.x ^ r.v2.x ^ r.v3.x ^ r.v4.x ^ r.v5.x ^ r.v6.x ^ r.v7.x;
-      l_run += __builtin_bit_cast(float, x & 0x3f800000u) + (float)kp[0];
-      const int64_t kn = key0 + NWAVE * TILE;
-      if (kn < c1) load_tile(kn);
-      key0 = kn;
-      continue;
-    }
-#endif
     wave_lds_sync();  // previous tile's LDS reads are done before it is overwritten
     store_tile();
     const int64_t key_next = key0 + NWAVE * TILE;

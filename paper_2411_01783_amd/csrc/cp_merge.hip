@@ -96,7 +96,9 @@ __global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float*
                                : (STRIDED ? parts_lse[s * part_stride_rows + row] : ptrs.lse[s][row]);
         const float w = __expf(x - lmax);  // exp(-inf) = 0 for empty partials
         den += w;
-        if (w != 0.f) {
+        // split-KV scratch rows are always written (zeros when empty), so their loads need
+        // not wait for the weights; caller-supplied partials with zero weight are not read
+        if (STRIDED || w != 0.f) {
           const TP* p = STRIDED ? (const TP*)(parts_out + (s * part_stride_rows + row) * head_dim)
                                 : (const TP*)ptrs.out[s] + row * head_dim;
           float x4[VEC];
