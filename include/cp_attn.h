@@ -228,6 +228,45 @@ int cp_ring_passq_decode(const cp_ring_desc* desc, void* stream);
 /* Workspace the ring drivers need: the maximum over all (query rank, KV rank) calls. */
 size_t cp_ring_workspace_bytes(const cp_ring_desc* desc, int32_t decode);
 
+/* Ring order chosen by cp_select_order. */
+typedef enum { CP_ORDER_PASS_KV = 0, CP_ORDER_PASS_Q = 1 } cp_ring_order;
+
+/* Which rule cp_select_order applies. */
+typedef enum {
+  CP_RULE_ANALYTIC = 0,        /* Algorithm 1 (Section 3.3): Equations 1 and 2 */
+  CP_RULE_ANALYTIC_ALL2ALL = 1,/* Algorithm 5 (Appendix C): Equation 1 tightened by the All2All cost */
+  CP_RULE_EMPIRICAL = 2        /* Appendix D: sign of h(T, P) = alpha ln T + beta ln(T/(T+P)) + gamma */
+} cp_select_rule;
+
+/* Model and system constants of the selection rules (host memory, read only). */
+typedef struct {
+  int32_t n_q_heads;      /* N_H  of the whole model (or of one GPU: only the ratio matters) */
+  int32_t n_kv_heads;     /* N_KV */
+  int32_t n_ranks;        /* N: CP ranks (nodes) the ring spans */
+  int32_t reserved;       /* must be 0 */
+  double peak_flops;      /* C: attainable attention FLOP/s of one rank */
+  double bandwidth;       /* BW: bytes/s of the link that carries the ring messages */
+  double bytes_per_elem;  /* e: 2 for bf16 */
+  double alpha, beta, gamma; /* CP_RULE_EMPIRICAL only; all three 0 = the paper's fit
+                                (-1.059, 1.145, 12.112) */
+} cp_select_params;
+
+/*
+ * pass-KV or pass-Q for a prefill of t_new tokens on top of p_cached cached tokens
+ * (full prefill: p_cached = 0; decode: t_new = 1). Pure host arithmetic, no GPU.
+ *   CP_RULE_ANALYTIC (Algorithm 1): pass-KV iff
+ *       T >= N * C * N_KV * e / (2 * N_H * BW)          (Equation 2: KV transfer hidden)
+ *    or T / (T + P) >= 2 * N_KV / N_H                   (Equation 1: KV message not larger)
+ *   CP_RULE_ANALYTIC_ALL2ALL (Algorithm 5): the second test becomes
+ *       T / (T + P) >= 2 * N_KV / N_H - 4 * T * BW / (N * C * e).
+ *   CP_RULE_EMPIRICAL (Appendix D): pass-KV iff h(T, P) > 0, natural logarithms.
+ * *order_out receives a cp_ring_order. Errors: CP_ERR_NULL; CP_ERR_SHAPE for t_new < 1,
+ * p_cached < 0, non-positive heads / ranks / C / BW / e; CP_ERR_UNSUPPORTED for an
+ * unknown rule.
+ */
+int cp_select_order(const cp_select_params* params, int64_t t_new, int64_t p_cached,
+                    int32_t rule, int32_t* order_out);
+
 /* Static description of a cp_status. Never NULL. */
 const char* cp_strerror(int status);
 

@@ -13,6 +13,8 @@ from .cp_oracle import (  # noqa: F401
     ring_passkv,
     ring_passq,
     ring_passq_decode,
+    roofline_latencies,
+    select_order,
     set_num_threads,
     shard_decode_batch,
     shard_partial_prefill,

@@ -16,6 +16,9 @@ bookkeeping that follows the paper's own steps:
                              query's source rank (the All2All) before merging.
 * `ring_passq_decode`      - Algorithm 4 (batched ring pass-Q decode) with the
                              batch ids travelling with the queries.
+* `select_order`           - pass-KV / pass-Q choice (Section 3.3 Algorithm 1,
+                             Appendix C Algorithm 5, Appendix D) from the roofline
+                             latencies of Table 1, not from the rearranged tests.
 """
 from __future__ import annotations
 
@@ -339,3 +342,52 @@ def ring_passq_decode(q, bid, q_pos, k, v, kv_pos, cu_kv, scale: Optional[float]
         out.append(o)
         lse.append(l)
     return out, lse, part_o, part_l
+
+
+# ---------------------------------------------------------------------------
+# pass-KV vs pass-Q (host logic)
+# ---------------------------------------------------------------------------
+
+def roofline_latencies(t_new: int, p_cached: int, n_q_heads: int, n_kv_heads: int, n_ranks: int,
+                       peak_flops: float, bandwidth: float, bytes_per_elem: float = 2.0,
+                       head_dim_total: float = 1.0):
+    """Table 1 per ring step on N ranks: (attention, Q message, KV message, All2All) seconds.
+
+    `head_dim_total` is D (model dimension); it multiplies every entry alike and cancels in
+    every comparison, so any positive value gives the same decisions. The All2All row is
+    Appendix C's (D + 1) T e / BW with the paper's D + 1 ~ D.
+    """
+    T, P, D, e = float(t_new), float(p_cached), float(head_dim_total), float(bytes_per_elem)
+    flops = 4.0 * T * D * (T + P)
+    q_bytes = T * D * e
+    kv_bytes = 2.0 * (T + P) * D * (n_kv_heads / n_q_heads) * e
+    attn = flops / (n_ranks * peak_flops)
+    return attn, q_bytes / bandwidth, kv_bytes / bandwidth, T * D * e / bandwidth
+
+
+def select_order(t_new: int, p_cached: int, n_q_heads: int, n_kv_heads: int, n_ranks: int,
+                 peak_flops: float = 0.0, bandwidth: float = 0.0, bytes_per_elem: float = 2.0,
+                 rule: str = "analytic", alpha: float = -1.059, beta: float = 1.145,
+                 gamma: float = 12.112) -> str:
+    """"pass-KV" or "pass-Q".
+
+    analytic (Algorithm 1): pass-KV when the KV message of a ring step hides under the
+    attention of that step, or when the KV message is not larger than the Q message.
+    all2all (Algorithm 5): the size test is replaced by "the exposed part of the KV
+    message is smaller than pass-Q's All2All of (O, LSE)".
+    empirical (Appendix D): sign of alpha ln T + beta ln(T / (T + P)) + gamma; the
+    paper does not say which logarithm: natural is assumed.
+    """
+    if rule == "empirical":
+        import math
+        h = alpha * math.log(t_new) + beta * math.log(t_new / (t_new + p_cached)) + gamma
+        return "pass-KV" if h > 0.0 else "pass-Q"
+    attn, q_msg, kv_msg, a2a = roofline_latencies(t_new, p_cached, n_q_heads, n_kv_heads,
+                                                  n_ranks, peak_flops, bandwidth, bytes_per_elem)
+    if attn >= kv_msg:
+        return "pass-KV"
+    if rule == "analytic":
+        return "pass-KV" if q_msg >= kv_msg else "pass-Q"
+    if rule == "all2all":
+        return "pass-Q" if kv_msg - attn > a2a else "pass-KV"
+    raise ValueError(rule)

@@ -25,7 +25,7 @@ CP_MAX_PARTS = 64
 EXPORTS = [
     "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_decode",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
-    "cp_ring_workspace_bytes", "cp_strerror", "cp_version",
+    "cp_ring_workspace_bytes", "cp_select_order", "cp_strerror", "cp_version",
 ]
 
 _vp = ctypes.c_void_p
@@ -51,6 +51,17 @@ class cp_ring_desc(ctypes.Structure):
                 ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t),
                 ("batch", _i32),
                 ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp))]
+
+
+class cp_select_params(ctypes.Structure):
+    _fields_ = [("n_q_heads", _i32), ("n_kv_heads", _i32), ("n_ranks", _i32), ("reserved", _i32),
+                ("peak_flops", ctypes.c_double), ("bandwidth", ctypes.c_double),
+                ("bytes_per_elem", ctypes.c_double), ("alpha", ctypes.c_double),
+                ("beta", ctypes.c_double), ("gamma", ctypes.c_double)]
+
+
+CP_ORDER_PASS_KV, CP_ORDER_PASS_Q = 0, 1
+CP_RULE_ANALYTIC, CP_RULE_ANALYTIC_ALL2ALL, CP_RULE_EMPIRICAL = 0, 1, 2
 
 
 class CpError(RuntimeError):
@@ -95,6 +106,9 @@ def load() -> ctypes.CDLL:
         fn.argtypes = [ctypes.POINTER(cp_ring_desc), _vp]
     lib.cp_ring_workspace_bytes.restype = ctypes.c_size_t
     lib.cp_ring_workspace_bytes.argtypes = [ctypes.POINTER(cp_ring_desc), _i32]
+    lib.cp_select_order.restype = ctypes.c_int
+    lib.cp_select_order.argtypes = [ctypes.POINTER(cp_select_params), _i64, _i64, _i32,
+                                    ctypes.POINTER(_i32)]
     _lib = lib
     return lib
 
@@ -156,6 +170,19 @@ def cp_shard_positions(total: int, n_ranks: int, rank: int, offset: int = 0) -> 
                                   pos.ctypes.data_as(ctypes.POINTER(_i32)), ctypes.byref(n)),
            "cp_shard_positions")
     return pos
+
+
+def cp_select_order(t_new: int, p_cached: int, n_q_heads: int, n_kv_heads: int, n_ranks: int,
+                    peak_flops: float = 0.0, bandwidth: float = 0.0, bytes_per_elem: float = 2.0,
+                    rule: int = CP_RULE_ANALYTIC, alpha: float = 0.0, beta: float = 0.0,
+                    gamma: float = 0.0) -> int:
+    """CP_ORDER_PASS_KV or CP_ORDER_PASS_Q for t_new tokens on p_cached cached (host only)."""
+    prm = cp_select_params(n_q_heads, n_kv_heads, n_ranks, 0, peak_flops, bandwidth,
+                           bytes_per_elem, alpha, beta, gamma)
+    order = _i32(-1)
+    _check(load().cp_select_order(ctypes.byref(prm), t_new, p_cached, rule, ctypes.byref(order)),
+           "cp_select_order")
+    return int(order.value)
 
 
 def cp_workspace_bytes(shape: cp_shape, kind: int) -> int:

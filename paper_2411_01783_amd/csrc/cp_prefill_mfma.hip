@@ -54,7 +54,11 @@ constexpr int OUT_STRIDE = D * 4 + 16;    // epilogue staging: one fp32 output r
 static_assert(NWAVE * 32 * OUT_STRIDE <= OFF_POS, "epilogue staging aliases the tile buffers");
 static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget of one CU");
 constexpr float kRescaleSlack = 8.f;  // log2 units
-constexpr int kReadAhead = 8;         // LDS fragment reads in flight ahead of their MFMA
+constexpr int kReadAhead = 8;
+#ifndef CP_MIN_TILES_PER_SPLIT
+#define CP_MIN_TILES_PER_SPLIT 1
+#endif
+constexpr int kMinTilesPerSplit = CP_MIN_TILES_PER_SPLIT;         // LDS fragment reads in flight ahead of their MFMA
 
 struct Params {
   const bf16_t* q;
@@ -535,11 +539,11 @@ Plan make_plan(const cp_shape& s) {
   pl.n_tiles = (int)((s.total_kv + TILE - 1) / TILE);
   pl.n_row_blocks = (int)((rows + BM - 1) / BM);
   // Split the KV axis when the row blocks alone cannot occupy the 256 CUs. Every split
-  // costs one fp32 partial of the output, so keep at least 4 tiles (512 keys) per split.
+  // costs one fp32 partial of the output, so keep at least kMinTilesPerSplit tiles per split.
   const int64_t wgs = (int64_t)pl.n_row_blocks * s.n_kv_heads;
   int splits = 1;
-  if (wgs > 0 && wgs < 128 && pl.n_tiles >= 8) {
-    splits = (int)std::min<int64_t>((256 + wgs - 1) / wgs, pl.n_tiles / 4);
+  if (wgs > 0 && wgs < 128 && pl.n_tiles >= 2 * kMinTilesPerSplit) {
+    splits = (int)std::min<int64_t>((256 + wgs - 1) / wgs, pl.n_tiles / kMinTilesPerSplit);
     splits = std::max(1, std::min(splits, CP_MAX_PARTS));
   }
   pl.tiles_per_split = pl.n_tiles > 0 ? (pl.n_tiles + splits - 1) / splits : 1;

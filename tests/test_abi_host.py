@@ -174,3 +174,36 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2411_01783_amd" not in text and "cp_attn.h" not in text, f
+
+
+def test_select_order_matches_oracle(lib, oracle):
+    names = {B.CP_ORDER_PASS_KV: "pass-KV", B.CP_ORDER_PASS_Q: "pass-Q"}
+    rules = {B.CP_RULE_ANALYTIC: "analytic", B.CP_RULE_ANALYTIC_ALL2ALL: "all2all",
+             B.CP_RULE_EMPIRICAL: "empirical"}
+    rng = np.random.default_rng(7)
+    for _ in range(400):
+        t = int(rng.integers(1, 200_000))
+        p = int(rng.integers(0, 2_000_000))
+        nkv = int(rng.choice([1, 2, 8]))
+        nh = nkv * int(rng.choice([1, 2, 4, 16]))
+        n = int(rng.choice([1, 2, 4, 8, 16]))
+        c = float(rng.uniform(1e14, 3e15))
+        bw = float(rng.uniform(1e10, 1e12))
+        for rule, rname in rules.items():
+            got = B.cp_select_order(t, p, nh, nkv, n, c, bw, 2.0, rule)
+            want = oracle.select_order(t, p, nh, nkv, n, c, bw, 2.0, rname)
+            assert names[got] == want, (t, p, nh, nkv, n, c, bw, rname)
+
+
+def test_select_order_rejects_bad_arguments(lib):
+    prm = B.cp_select_params(16, 1, 4, 0, 1e15, 1e11, 2.0, 0.0, 0.0, 0.0)
+    out = ctypes.c_int32(-1)
+    f = lib.cp_select_order
+    assert f(None, 1, 0, 0, ctypes.byref(out)) == -1
+    assert f(ctypes.byref(prm), 1, 0, 0, None) == -1
+    assert f(ctypes.byref(prm), 0, 0, 0, ctypes.byref(out)) == -2
+    assert f(ctypes.byref(prm), 1, -1, 0, ctypes.byref(out)) == -2
+    assert f(ctypes.byref(prm), 1, 0, 9, ctypes.byref(out)) == -3
+    bad = B.cp_select_params(16, 1, 4, 0, 0.0, 1e11, 2.0, 0.0, 0.0, 0.0)
+    assert f(ctypes.byref(bad), 1, 0, 0, ctypes.byref(out)) == -2
+    assert f(ctypes.byref(bad), 1, 0, 2, ctypes.byref(out)) == 0   # empirical rule needs no C / BW

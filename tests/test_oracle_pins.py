@@ -434,3 +434,88 @@ def test_pins_detect_planted_mistakes(oracle):
     # transposed mask (key sees query)
     o, _ = oracle.attn(q, k, v, -pos, -pos)
     assert not np.allclose(o, good_o)
+
+
+# ---------------------------------------------------------------------------
+# pass-KV / pass-Q selection (Section 3.3, Appendix C, Appendix D)
+# ---------------------------------------------------------------------------
+
+LLAMA405 = dict(n_q_heads=128, n_kv_heads=8)
+CP4 = dict(n_ranks=4, peak_flops=16640.0, bandwidth=1.0, bytes_per_elem=2.0)  # C / BW = 16640
+
+
+def test_selector_matches_the_papers_validation_points(oracle):
+    path = os.path.join(os.path.dirname(__file__), "golden", "selector_cp4_128k.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 6
+    for t, p, want in rows:
+        assert oracle.select_order(int(t), int(p), **LLAMA405, **CP4) == want, (t, p)
+
+
+def test_selector_miss_rate_threshold_is_twice_the_head_ratio(oracle):
+    # Equation 1 alone (a link so slow that Equation 2 never holds): 12.5 % for 128 / 8 heads
+    slow = dict(n_ranks=4, peak_flops=1e30, bandwidth=1.0)
+    total = 1_000_000
+    assert oracle.select_order(124_999, total - 124_999, **LLAMA405, **slow) == "pass-Q"
+    assert oracle.select_order(125_001, total - 125_001, **LLAMA405, **slow) == "pass-KV"
+    # MHA (N_H = N_KV): the threshold 2 exceeds any miss rate, Q is always the smaller message
+    assert oracle.select_order(total, 0, n_q_heads=8, n_kv_heads=8, **slow) == "pass-Q"
+    # full prefill of a GQA model with N_H > 2 N_KV passes KV; decode passes Q (Section 3.3)
+    assert oracle.select_order(total, 0, **LLAMA405, **slow) == "pass-KV"
+    assert oracle.select_order(1, 131072, **LLAMA405, **CP4) == "pass-Q"
+
+
+def test_selector_overlap_threshold_is_independent_of_the_cache(oracle):
+    # Equation 2: the T threshold does not depend on P and scales with N
+    for p in (10**5, 10**6, 10**7):
+        assert oracle.select_order(4159, p, **LLAMA405, **CP4) == "pass-Q"
+        assert oracle.select_order(4161, p, **LLAMA405, **CP4) == "pass-KV"
+    cp8 = dict(CP4, n_ranks=8)
+    assert oracle.select_order(8319, 10**6, **LLAMA405, **cp8) == "pass-Q"
+    assert oracle.select_order(8321, 10**6, **LLAMA405, **cp8) == "pass-KV"
+
+
+def test_selector_roofline_rows_are_table_1(oracle):
+    # FLOPS 4 T D (T + P), Q bytes T D e, KV bytes 2 (P + T) D (N_KV / N_H) e
+    attn, q_msg, kv_msg, a2a = oracle.roofline_latencies(
+        1000, 7000, 16, 2, n_ranks=2, peak_flops=1e3, bandwidth=10.0, bytes_per_elem=2.0,
+        head_dim_total=64.0)
+    assert attn == 4 * 1000 * 64 * 8000 / (2 * 1e3)
+    assert q_msg == 1000 * 64 * 2 / 10.0
+    assert kv_msg == 2 * 8000 * 64 * (2 / 16) * 2 / 10.0
+    assert a2a == q_msg
+
+
+def test_selector_all2all_lowers_the_pass_q_region(oracle):
+    # Appendix C: counting the All2All can only move decisions from pass-Q to pass-KV, and at
+    # 2.5 % miss rate on CP4 (T = 3200) pass-Q still wins, as the paper measures
+    assert oracle.select_order(3200, 124800, **LLAMA405, **CP4, rule="all2all") == "pass-Q"
+    moved = 0
+    for t in range(200, 6000, 100):
+        for total in (16000, 64000, 128000, 512000):
+            if t >= total:
+                continue
+            a = oracle.select_order(t, total - t, **LLAMA405, **CP4)
+            b = oracle.select_order(t, total - t, **LLAMA405, **CP4, rule="all2all")
+            assert not (a == "pass-KV" and b == "pass-Q")
+            moved += a != b
+    assert moved > 0
+
+
+def test_selector_empirical_threshold_grows_with_t(oracle):
+    # Appendix D: for each T there is a miss-rate threshold, and it increases with T
+    def threshold(t):
+        lo = None
+        for miss in np.geomspace(1e-4, 1.0, 400):
+            p = int(round(t / miss)) - t
+            if p < 0:
+                continue
+            if oracle.select_order(t, p, 128, 8, 4, rule="empirical") == "pass-KV":
+                lo = miss
+                break
+        return lo
+    th = [threshold(t) for t in (500, 1000, 2000, 4000, 8000)]
+    assert all(x is not None for x in th)
+    assert all(a < b for a, b in zip(th, th[1:]))
+    # the fitted line puts the paper's measured pass-Q point (T = 3200, 2.5 %) on the pass-Q side
+    assert oracle.select_order(3200, 124800, 128, 8, 4, rule="empirical") == "pass-Q"
