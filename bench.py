@@ -110,6 +110,30 @@ def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
                 merge_bytes=merge_bytes / len(ranks))
 
 
+def per_call_prefill(w: W.Workload, st: dict, reps: int = 8):
+    """One cp_attn_partial call at its real shape: an off-diagonal ring step (half of the
+    query rows see the whole shard, the others nothing) and the diagonal step."""
+    ring = st["ring"]
+    out = {}
+    kq = w.n_ranks // 2
+    for label, s in (("off_diagonal", (kq + 5) % w.n_ranks), ("diagonal", kq)):
+        def call():
+            B.cp_attn_partial(st["qs"][kq], st["ks"][s], st["vs"][s], st["ps"][kq], st["ps"][s],
+                              out=ring.partial_out[s], lse=ring.partial_lse[s],
+                              workspace=ring.workspace)
+        call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        flop = 4.0 * w.head_dim * w.n_q_heads * visible_pairs(st["pos"][kq], st["pos"][s])
+        out[label] = {"us": round(us, 1), "tflops": round(flop / us / 1e6, 1)}
+    return out
+
+
 def cpu_baseline_prefill(w: W.Workload, st: dict, n_tokens: int = 1024):
     """fp64 oracle on a seeded sample of query tokens of the same sequence (all heads)."""
     import oracle
@@ -159,7 +183,7 @@ def build_decode(w: W.Workload):
     return dict(ranks=ranks, q=q, q_pos=q_pos, bid=bid, lengths=lengths)
 
 
-def bench_decode(w: W.Workload, reps: int = 20):
+def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False):
     st = build_decode(w)
     n = w.n_ranks
     shape = B.make_shape(B.CP_BF16, w.head_dim, w.n_q_heads, w.n_kv_heads, w.batch,
@@ -177,9 +201,75 @@ def bench_decode(w: W.Workload, reps: int = 20):
     sec = time_steps(one_pass, reps, 3)
     kv_bytes = sum(2 * r["total"] * w.n_kv_heads * w.head_dim * 2 for r in st["ranks"])
     io_bytes = n * (st["q"].numel() * 2 + out.numel() * 4 + lse.numel() * 4)
-    return dict(workload=w.name, ms_per_rank=sec * 1e3 / n, gbs=(kv_bytes + io_bytes) / sec / 1e9,
-                frac_hbm=(kv_bytes + io_bytes) / sec / 1e9 / PEAK_HBM_GBS,
-                kv_mb_per_rank=kv_bytes / n / 1e6)
+    res = dict(workload=w.name, ms_per_rank=sec * 1e3 / n, gbs=(kv_bytes + io_bytes) / sec / 1e9,
+               frac_hbm=(kv_bytes + io_bytes) / sec / 1e9 / PEAK_HBM_GBS,
+               kv_mb_per_rank=kv_bytes / n / 1e6)
+    if graph:
+        # the same 16-rank sequence replayed from one HIP graph (the paper runs decode under
+        # graphs, Section 4.3); the library records kernels only, no memset nodes
+        ref = out.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            one_pass()
+            side.synchronize()
+            g.capture_begin(capture_error_mode="relaxed")
+            one_pass()
+            g.capture_end()
+        torch.cuda.synchronize()
+        gsec = time_steps(g.replay, reps, 3)
+        res["graph_ms_per_rank"] = gsec * 1e3 / n
+        res["graph_gbs"] = (kv_bytes + io_bytes) / gsec / 1e9
+        res["graph_matches_eager"] = bool(torch.equal(ref, out))
+    return res
+
+
+# ---------------------------------------------------------------------------
+# persistent-KV partial prefill, pass-Q (aux; launch-bound at small T)
+# ---------------------------------------------------------------------------
+
+def bench_partial_prefill(names, reps: int = 5):
+    rows = []
+    for name in names:
+        w = W.WORKLOADS[name]
+        q, k, v = W.qkv(w, device="cuda")
+        n, p_cached, t_new = w.n_ranks, w.p_cached, w.t_new
+        qpos, kvpos = [], []
+        for r in range(n):
+            qp = B.cp_shard_positions(t_new, n, r, offset=p_cached)
+            qpos.append(qp)
+            kvpos.append(np.concatenate([B.cp_shard_positions(p_cached, n, r), qp]))
+
+        def take(t, pos):
+            return t[torch.as_tensor(pos.astype(np.int64)).to("cuda")].contiguous()
+        ring = B.Ring([take(q, pp - p_cached) for pp in qpos], [take(k, pp) for pp in kvpos],
+                      [take(v, pp) for pp in kvpos], [_i32(pp) for pp in qpos],
+                      [_i32(pp) for pp in kvpos], out_dtype=torch.bfloat16)
+        flop = 4.0 * w.head_dim * w.n_q_heads * (t_new * p_cached + t_new * (t_new + 1) // 2)
+        row = {"workload": name, "t_new": t_new, "p_cached": p_cached}
+        for label, fn in (("passq", B.cp_ring_passq), ("passkv", B.cp_ring_passkv)):
+            sec = time_steps(lambda: fn(ring), reps, 2)
+            row[label + "_ms_per_ring"] = round(sec * 1e3, 3)
+            row[label + "_us_per_call"] = round(sec * 1e6 / (n * n), 2)
+            row[label + "_tflops"] = round(flop / sec / 1e12, 1)
+        rows.append(row)
+        del ring, q, k, v
+        torch.cuda.empty_cache()
+    return rows
+
+
+def selector_table(c_flops: float):
+    """Orders cp_select_order picks for the partial-prefill workloads, with C = the
+    attention rate measured above and BW = one xGMI link (153 GB/s) or a 50 GB/s NIC."""
+    out = []
+    for bw_name, bw in (("xgmi_153GBs", 153e9), ("nic_50GBs", 50e9)):
+        for t in (128, 1024, 2048, 8192, 16384, 131072):
+            p = 131072 if t < 131072 else 0
+            order = B.cp_select_order(t, p, 128, 8, 16, c_flops, bw, 2.0, B.CP_RULE_ANALYTIC)
+            out.append({"link": bw_name, "t_new": t, "p_cached": p,
+                        "order": "pass-KV" if order == B.CP_ORDER_PASS_KV else "pass-Q"})
+    return out
 
 
 # ---------------------------------------------------------------------------
@@ -272,14 +362,20 @@ def main():
                           "frac_hbm": round(kp["merge_bytes"] / (kp["merge_ms"] * 1e-3) / 1e9 /
                                             PEAK_HBM_GBS, 4)}},
     }
+    result["aux"]["per_call"] = per_call_prefill(w, st)
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline_prefill(w, st)
     del st, ring
     torch.cuda.empty_cache()
     if not args.no_aux:
-        d = bench_decode(W.WORKLOADS["decode_b32"])
+        d = bench_decode(W.WORKLOADS["decode_b32"], graph=True)
         result["aux"]["decode"] = {k: (round(v, 4) if isinstance(v, float) else v)
                                    for k, v in d.items()}
+        torch.cuda.empty_cache()
+        result["aux"]["partial_prefill"] = bench_partial_prefill(
+            ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
+             "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"])
+        result["aux"]["selector"] = selector_table(tflops * 1e12)
     print(json.dumps(result))
 
 
