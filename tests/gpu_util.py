@@ -1,4 +1,7 @@
 """Helpers shared by the GPU parity tests: tolerance checks and oracle/GPU plumbing."""
+import json
+import os
+
 import numpy as np
 import torch
 
@@ -37,10 +40,18 @@ def check(out, lse, ref_o, ref_l, o_atol=O_ATOL_BF16, lse_rtol=LSE_RTOL, what=""
     err_o = np.abs(o - ref_o).max() if o.size else 0.0
     assert err_o <= o_atol, "%s: max-abs O error %.3e > %.1e" % (what, err_o, o_atol)
     fin = ~empty
+    rel_l = 0.0
     if fin.any():
         tol = lse_rtol * np.maximum(1.0, np.abs(ref_l[fin]))
         err_l = np.abs(l[fin] - ref_l[fin])
+        rel_l = float((err_l / np.maximum(1.0, np.abs(ref_l[fin]))).max())
         assert np.all(err_l <= tol), "%s: LSE error %.3e" % (what, (err_l / tol).max() * lse_rtol)
+    log = os.environ.get("CP_PARITY_LOG")
+    if log:  # measured errors of every comparison, one JSON line each (for the results table)
+        with open(log, "a") as f:
+            f.write(json.dumps({"test": os.environ.get("PYTEST_CURRENT_TEST", ""), "what": what,
+                                "rows": int(l.size), "max_abs_o": float(err_o),
+                                "max_rel_lse": rel_l}) + "\n")
     return err_o
 
 
