@@ -115,6 +115,13 @@ size_t cp_workspace_bytes(const cp_shape* shape, int32_t kind);
  * bf16 inputs with head_dim 128 run on the MFMA kernel (fully masked KV tiles
  * are skipped; short query shards are split over the KV axis through the
  * workspace). Other combinations run on an fp32 vector kernel.
+ *
+ * Packed batches (the fused variable-length inputs of Algorithm 2, Section 3.4):
+ * query i of sequence b sees key j iff j belongs to sequence b and
+ * kv_pos[j] <= q_pos[i]. On the MFMA kernel the sequences are told apart by
+ * shifting sequence b's positions by the sum over earlier sequences of
+ * (1 + largest position in it); that sum over the whole batch must stay below
+ * 2^31 - 1 (sequences past the limit would see nothing).
  */
 int cp_attn_partial(const cp_shape* shape, const void* q, const void* k, const void* v,
                     const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_q,

@@ -31,8 +31,7 @@ inline float resolve_scale(float scale, int head_dim) {
 }
 
 inline bool mfma_prefill_applies(const cp_shape& s) {
-  return s.dtype == CP_BF16 && s.head_dim == 128 && s.batch == 1 &&
-         (s.n_q_heads / s.n_kv_heads) <= 64;
+  return s.dtype == CP_BF16 && s.head_dim == 128 && (s.n_q_heads / s.n_kv_heads) <= 64;
 }
 
 inline size_t elem_size(int32_t dtype) { return dtype == CP_FP32 ? 4 : 2; }
@@ -79,7 +78,11 @@ size_t cp_workspace_bytes(const cp_shape* shape, int32_t kind) {
   if (check_shape(shape) != CP_OK) return 0;
   switch (kind) {
     case CP_WS_PARTIAL:
-      return mfma_prefill_applies(*shape) ? prefill_mfma_workspace_bytes(*shape) : 0;
+      if (!mfma_prefill_applies(*shape)) return 0;
+      return prefill_mfma_workspace_bytes(*shape) +
+             (shape->batch > 1
+                  ? varseq_layout(shape->batch, shape->total_q, shape->total_kv).total
+                  : 0);
     case CP_WS_DECODE:
       return decode_workspace_bytes(*shape);
     default:
@@ -105,12 +108,28 @@ int cp_attn_partial(const cp_shape* shape, const void* q, const void* k, const v
   if (s.total_q == 0) return CP_OK;
   const float scale = resolve_scale(s.softmax_scale, s.head_dim);
   hipStream_t st = (hipStream_t)stream;
-  if (mfma_prefill_applies(s) && cu_seqlens_q == nullptr) {
+  if (mfma_prefill_applies(s) && (cu_seqlens_q == nullptr || s.batch == 1)) {
     const size_t need = prefill_mfma_workspace_bytes(s);
     if (need > 0 && (workspace == nullptr || !aligned256(workspace) || workspace_bytes < need))
       return CP_ERR_WORKSPACE;
     return launch_prefill_mfma(s, scale, q, k, v, q_pos, kv_pos, out, lse, out_dtype, workspace,
-                               workspace_bytes, nullptr, st);
+                               workspace_bytes, nullptr, nullptr, st);
+  }
+  if (mfma_prefill_applies(s)) {
+    // packed batch: shift every sequence into its own position range, then one launch
+    if (s.total_q > 0x7fffffffLL || s.total_kv > 0x7fffffffLL) return CP_ERR_SHAPE;
+    const VarseqLayout vl = varseq_layout(s.batch, s.total_q, s.total_kv);
+    const size_t need = vl.total + prefill_mfma_workspace_bytes(s);
+    if (workspace == nullptr || !aligned256(workspace) || workspace_bytes < need)
+      return CP_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    if (launch_varseq_encode(s.batch, s.total_q, s.total_kv, q_pos, kv_pos, cu_seqlens_q,
+                             cu_seqlens_kv, ws, st) != CP_OK)
+      return CP_ERR_LAUNCH;
+    return launch_prefill_mfma(s, scale, q, k, v, (const int32_t*)(ws + vl.q_hi_off),
+                               (const int32_t*)(ws + vl.kv_off), out, lse, out_dtype,
+                               ws + vl.total, workspace_bytes - vl.total, nullptr,
+                               (const int32_t*)(ws + vl.q_lo_off), st);
   }
   return launch_partial_generic(s, scale, q, k, v, q_pos, kv_pos, cu_seqlens_q, cu_seqlens_kv,
                                 out, lse, out_dtype, st);
@@ -298,7 +317,7 @@ int ring_partial(const cp_ring_desc* d, const RingWork& w, bool decode, int a, i
     if (!aligned16(d->q[a]) || !aligned16(d->k[b]) || !aligned16(d->v[b])) return CP_ERR_ALIGN;
     return launch_prefill_mfma(s, resolve_scale(s.softmax_scale, s.head_dim), d->q[a], d->k[b],
                                d->v[b], d->q_pos[a], d->kv_pos[b], o, l, d->part_dtype, w.call_ws,
-                               w.call_ws_bytes, (char*)d->workspace + w.bounds_off[b], st);
+                               w.call_ws_bytes, (char*)d->workspace + w.bounds_off[b], nullptr, st);
   }
   return cp_attn_partial(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b], nullptr,
                          nullptr, o, l, d->part_dtype, w.call_ws, w.call_ws_bytes, st);

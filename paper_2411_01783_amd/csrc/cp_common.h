@@ -52,7 +52,16 @@ int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
-                        const void* tile_bounds, hipStream_t stream);
+                        const void* tile_bounds, const int32_t* q_lo, hipStream_t stream);
+
+// Packed batches on the MFMA path: per-sequence position ranges (see cp_varseq.hip).
+struct VarseqLayout {
+  size_t span_off, base_off, q_hi_off, q_lo_off, kv_off, total;
+};
+VarseqLayout varseq_layout(int32_t batch, int64_t total_q, int64_t total_kv);
+int launch_varseq_encode(int32_t batch, int64_t total_q, int64_t total_kv, const int32_t* q_pos,
+                         const int32_t* kv_pos, const int32_t* cu_q, const int32_t* cu_kv,
+                         void* workspace, hipStream_t stream);
 
 // split-KV decode, bf16, head_dim 128.
 size_t decode_workspace_bytes(const cp_shape& s);

@@ -48,7 +48,7 @@ constexpr int MAX_LIVE = 512;   // live-tile list entries per chunk (8 wavefront
 constexpr int OFF_VT = 2 * K_BYTES;
 constexpr int OFF_POS = OFF_VT + 2 * VT_BYTES;
 constexpr int OFF_SCRATCH = OFF_POS + 2 * POS_BYTES;
-constexpr int OFF_LIVE = OFF_SCRATCH + 64;
+constexpr int OFF_LIVE = OFF_SCRATCH + 128;  // scratch: 8 maxima, 1 count, 8 minima (ints)
 constexpr int SMEM_BYTES = OFF_LIVE + MAX_LIVE * 16;
 constexpr int OUT_STRIDE = D * 4 + 16;    // epilogue staging: one fp32 output row + pad
 static_assert(NWAVE * 32 * OUT_STRIDE <= OFF_POS, "epilogue staging aliases the tile buffers");
@@ -66,6 +66,7 @@ struct Params {
   const bf16_t* v;
   const int32_t* q_pos;
   const int32_t* kv_pos;
+  const int32_t* q_lo;    // BAND only: smallest visible key position per query token
   const int2* bounds;     // [n_tiles] (min, max) of kv_pos per tile
   void* out;              // final output (n_splits == 1)
   float* lse;
@@ -208,7 +209,9 @@ __device__ __forceinline__ void store_half(char* kbuf, char* vtbuf, int32_t* pos
     *(uint2*)(vtbuf + (i * 32 + dc) * VT_STRIDE + slot0 * 2) = t[i];
 }
 
-template <typename TO>
+// BAND: packed batch. Positions are shifted per sequence and a query also has a lower bound
+// q_lo (the shift of its sequence): visible iff q_lo <= kv_pos <= q_pos.
+template <typename TO, bool BAND>
 __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     Params p, const int2* __restrict__ tile_bounds) {
   // tile_bounds is a separate read-only, non-aliased argument so that it is fetched
@@ -234,6 +237,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   const int hg = row_ok ? (int)(r - token * p.group) : 0;
   const int64_t row_lin = (token * p.n_kv_heads + kvh) * p.group + hg;  // index into [tokens, N_H]
   const int32_t qp = row_ok ? p.q_pos[token] : CP_POS_PAD_Q;
+  const int32_t ql = BAND && row_ok ? p.q_lo[token] : INT32_MIN;
 
   bf16x8_t qf[8];
 #pragma unroll
@@ -245,16 +249,34 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
 
   // ---- query position range of the wavefront and of the workgroup ----
   int w_qmin = row_ok ? qp : INT32_MAX, w_qmax = qp;
+  // lower bounds of the rows that can see anything (a padded query has the empty range)
+  const bool sees = row_ok && qp >= 0;
+  int w_lomin = BAND && sees ? ql : INT32_MAX, w_lomax = BAND && sees ? ql : INT32_MIN;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     w_qmin = min(w_qmin, __shfl_xor(w_qmin, o, 64));
     w_qmax = max(w_qmax, __shfl_xor(w_qmax, o, 64));
+    if (BAND) {
+      w_lomin = min(w_lomin, __shfl_xor(w_lomin, o, 64));
+      w_lomax = max(w_lomax, __shfl_xor(w_lomax, o, 64));
+    }
   }
-  if (lane == 0) wg_scratch[wave] = w_qmax;
+  if (lane == 0) {
+    wg_scratch[wave] = w_qmax;
+    if (BAND) wg_scratch[NWAVE + 1 + wave] = w_lomin;
+  }
   __syncthreads();
-  int wg_qmax = INT32_MIN;
+  int wg_qmax = INT32_MIN, wg_lomin = INT32_MAX;
 #pragma unroll
-  for (int w = 0; w < NWAVE; ++w) wg_qmax = max(wg_qmax, wg_scratch[w]);
+  for (int w = 0; w < NWAVE; ++w) {
+    wg_qmax = max(wg_qmax, wg_scratch[w]);
+    if (BAND) wg_lomin = min(wg_lomin, wg_scratch[NWAVE + 1 + w]);
+  }
+  if (BAND) {
+    wg_lomin = __builtin_amdgcn_readfirstlane(wg_lomin);
+    w_lomin = __builtin_amdgcn_readfirstlane(w_lomin);
+    w_lomax = __builtin_amdgcn_readfirstlane(w_lomax);
+  }
   // wave-uniform by construction; say so, so that control flow stays on the scalar unit
   wg_qmax = __builtin_amdgcn_readfirstlane(wg_qmax);
   w_qmin = __builtin_amdgcn_readfirstlane(w_qmin);
@@ -286,7 +308,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
       bool lv = false;
       if (t < t_end) {
         b = tile_bounds[t];
-        lv = b.x <= wg_qmax;
+        lv = b.x <= wg_qmax && (!BAND || b.y >= wg_lomin);
       }
       const uint64_t mask = __builtin_amdgcn_ballot_w64(lv);
       if (lane == 0) wg_scratch[wave] = __builtin_popcountll(mask);
@@ -338,8 +360,9 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
       const bool next_two = has_next && next_key0 + SUB < p.total_kv;
       const bool two = tile * TILE + SUB < p.total_kv;
       // every key of the tile beyond this wavefront's queries: nothing to compute here
-      const bool wave_live = bmin <= w_qmax;
-      const bool need_mask = bmax > w_qmin || (tile + 1) * TILE > p.total_kv;
+      const bool wave_live = bmin <= w_qmax && (!BAND || bmax >= w_lomin);
+      const bool need_mask =
+          bmax > w_qmin || (tile + 1) * TILE > p.total_kv || (BAND && bmin < w_lomax);
 
       if (has_next) load_half(p, hoff, kvh, next_key0, tid, regs);
 
@@ -382,10 +405,10 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
 #pragma unroll
               for (int q4 = 0; q4 < 4; ++q4) {
                 const int4 kp = *(const int4*)(pb32 + kb2 * 32 + q4 * 8);  // 4 consecutive keys
-                if (kp.x > qp) s[kb2][q4 * 4 + 0] = -INFINITY;
-                if (kp.y > qp) s[kb2][q4 * 4 + 1] = -INFINITY;
-                if (kp.z > qp) s[kb2][q4 * 4 + 2] = -INFINITY;
-                if (kp.w > qp) s[kb2][q4 * 4 + 3] = -INFINITY;
+                if (kp.x > qp || (BAND && kp.x < ql)) s[kb2][q4 * 4 + 0] = -INFINITY;
+                if (kp.y > qp || (BAND && kp.y < ql)) s[kb2][q4 * 4 + 1] = -INFINITY;
+                if (kp.z > qp || (BAND && kp.z < ql)) s[kb2][q4 * 4 + 2] = -INFINITY;
+                if (kp.w > qp || (BAND && kp.w < ql)) s[kb2][q4 * 4 + 3] = -INFINITY;
               }
           }
 
@@ -578,7 +601,7 @@ int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
-                        const void* tile_bounds, hipStream_t stream) {
+                        const void* tile_bounds, const int32_t* q_lo, hipStream_t stream) {
   const Plan pl = make_plan(s);
   if (workspace_bytes < pl.bounds_bytes + pl.part_out_bytes + pl.part_lse_bytes)
     return CP_ERR_WORKSPACE;
@@ -588,7 +611,7 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
   char* ws = (char*)workspace;
   Params p;
   p.q = (const bf16_t*)q; p.k = (const bf16_t*)k; p.v = (const bf16_t*)v;
-  p.q_pos = q_pos; p.kv_pos = kv_pos;
+  p.q_pos = q_pos; p.kv_pos = kv_pos; p.q_lo = q_lo;
   p.bounds = tile_bounds != nullptr ? (const int2*)tile_bounds : (const int2*)ws;
   p.out = out; p.lse = lse;
   p.part_out = (float*)(ws + pl.bounds_bytes);
@@ -608,7 +631,10 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
 
   const dim3 grid(pl.n_row_blocks, s.n_kv_heads, pl.n_splits);
   const bool direct_bf16 = pl.n_splits == 1 && out_dtype == CP_BF16;
-  auto kern = direct_bf16 ? prefill_mfma_kernel<bf16_t> : prefill_mfma_kernel<float>;
+  auto kern = q_lo != nullptr
+                  ? (direct_bf16 ? prefill_mfma_kernel<bf16_t, true> : prefill_mfma_kernel<float, true>)
+                  : (direct_bf16 ? prefill_mfma_kernel<bf16_t, false>
+                                 : prefill_mfma_kernel<float, false>);
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                           SMEM_BYTES) != hipSuccess)
     return CP_ERR_LAUNCH;

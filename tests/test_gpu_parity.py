@@ -109,6 +109,54 @@ def test_mfma_partial_random_positions(oracle, tq, tkv, nh, nkv):
         check(o, l, *ref, what="out dtype %s" % odt)
 
 
+@pytest.mark.parametrize("nh,nkv", [(16, 1), (8, 2)])
+def test_mfma_packed_batch_random_positions(oracle, nh, nkv):
+    # Algorithm 2's fused variable-length inputs: several sequences in one call, one of them
+    # empty on both sides, one with queries but no keys; random (unsorted) positions whose
+    # ranges overlap between sequences, padded slots on both sides
+    cu_q = np.array([0, 37, 37, 300, 310, 700], dtype=np.int32)
+    cu_kv = np.array([0, 500, 500, 1300, 1300, 2100], dtype=np.int32)
+    tq, tkv = int(cu_q[-1]), int(cu_kv[-1])
+    q, q64 = randn(41, (tq, nh, 128))
+    k, k64 = randn(42, (tkv, nkv, 128))
+    v, v64 = randn(43, (tkv, nkv, 128))
+    rng = np.random.default_rng(44)
+    qp = rng.integers(-1, 900, size=tq)
+    kp = rng.integers(0, 900, size=tkv)
+    kp[rng.integers(0, tkv, size=9)] = B.CP_POS_PAD_KV
+    ref = oracle.attn(q64, k64, v64, qp, kp, cu_q=cu_q, cu_kv=cu_kv)
+    assert np.isneginf(ref[1][300:310]).all()       # the sequence without keys
+    for odt in (torch.float32, torch.bfloat16):
+        o, l = gpu_partial(q, k, v, qp, kp, cu_seqlens_q=i32(cu_q), cu_seqlens_kv=i32(cu_kv),
+                           out_dtype=odt)
+        check(o, l, *ref, what="packed batch, out dtype %s" % odt)
+
+
+def test_mfma_packed_batch_causal_prefill_with_cache_offsets(oracle):
+    # three sequences of different length, each a partial prefill: cached positions 0..P_b-1
+    # plus T_b new tokens at P_b..P_b+T_b-1; sorted positions, so every tile class occurs
+    # (skipped, unmasked, straddling a sequence boundary, straddling the diagonal)
+    p_cached = [0, 900, 130]
+    t_new = [700, 150, 260]
+    cu_q = np.concatenate([[0], np.cumsum(t_new)]).astype(np.int32)
+    cu_kv = np.concatenate([[0], np.cumsum([p + t for p, t in zip(p_cached, t_new)])]).astype(np.int32)
+    qp = np.concatenate([np.arange(p, p + t) for p, t in zip(p_cached, t_new)])
+    kp = np.concatenate([np.arange(0, p + t) for p, t in zip(p_cached, t_new)])
+    tq, tkv = int(cu_q[-1]), int(cu_kv[-1])
+    q, q64 = randn(51, (tq, 16, 128))
+    k, k64 = randn(52, (tkv, 1, 128))
+    v, v64 = randn(53, (tkv, 1, 128))
+    ref = oracle.attn(q64, k64, v64, qp, kp, cu_q=cu_q, cu_kv=cu_kv)
+    o, l = gpu_partial(q, k, v, qp, kp, cu_seqlens_q=i32(cu_q), cu_seqlens_kv=i32(cu_kv),
+                       out_dtype=torch.float32)
+    check(o, l, *ref, what="packed causal prefill")
+    # the same rows through one call per sequence (batch 1) must agree with the oracle too
+    for b in range(3):
+        qs, ks = slice(cu_q[b], cu_q[b + 1]), slice(cu_kv[b], cu_kv[b + 1])
+        o1, l1 = gpu_partial(q[qs], k[ks], v[ks], qp[qs], kp[ks], out_dtype=torch.float32)
+        check(o1, l1, ref[0][qs], ref[1][qs], what="sequence %d alone" % b)
+
+
 def test_mfma_partial_sorted_positions_all_tile_classes(oracle):
     # natural causal order: tiles are skipped, unmasked, or diagonal depending on the row block
     t = 700
