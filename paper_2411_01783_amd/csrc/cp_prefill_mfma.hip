@@ -55,6 +55,10 @@ static_assert(NWAVE * 32 * OUT_STRIDE <= OFF_POS, "epilogue staging aliases the 
 static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget of one CU");
 constexpr float kRescaleSlack = 8.f;  // log2 units
 constexpr int kReadAhead = 8;
+#ifndef CP_DL_READ_AHEAD_V
+#define CP_DL_READ_AHEAD_V 4
+#endif
+constexpr int kReadAheadV = CP_DL_READ_AHEAD_V;  // V^T fragments (two transposed reads each) in flight
 #ifndef CP_MIN_TILES_PER_SPLIT
 #define CP_MIN_TILES_PER_SPLIT 1
 #endif
@@ -548,6 +552,386 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Direct-to-LDS variant. K and V tiles travel HBM/L2 -> LDS with global_load_lds (16 bytes
+// per lane, no register staging, no LDS store instructions, no register transposes):
+//   - both tiles are stored row-major [key][256 B], unpadded (a wavefront instruction
+//     writes 64 x 16 B contiguously, i.e. four whole rows); bank conflicts are avoided by
+//     permuting the 16-byte chunks of a row on the GLOBAL side: chunk c of K row r lands at
+//     chunk position c ^ (r & 15), chunk c of V row r at c ^ ((r & 3) * 4);
+//   - K fragments (rows = keys) are read with ds_read_b128 as before;
+//   - V^T fragments (rows = channels, k = keys) are read with ds_read_b64_tr_b16, which
+//     hands lane i of a 16-lane group element (i % 4) of what lanes 4j + i / 4 (j = 0..3)
+//     of the group addressed: four lanes address four consecutive keys of a 16-channel
+//     strip, and every lane receives one channel of those four keys.
+// Accumulator (db, i) of lane (n, g) is channel db*32 + (i/4)*8 + g*4 + i%4 of query n.
+// ---------------------------------------------------------------------------------------
+#define CP_LDS_AS __attribute__((address_space(3)))
+#define CP_GLB_AS __attribute__((address_space(1)))
+typedef short shortx4_t __attribute__((ext_vector_type(4)));
+
+constexpr int ROW_BYTES = D * 2;              // one K or V row in LDS
+constexpr int KD_BYTES = TILE * ROW_BYTES;    // 32 KiB per tile buffer
+constexpr int OFF_V8 = 2 * KD_BYTES;
+constexpr int OFF_POS8 = OFF_V8 + 2 * KD_BYTES;
+constexpr int OFF_SCRATCH8 = OFF_POS8 + 2 * POS_BYTES;
+constexpr int OFF_LIVE8 = OFF_SCRATCH8 + 128;
+constexpr int SMEM_BYTES8 = OFF_LIVE8 + MAX_LIVE * 16;
+static_assert(NWAVE * 32 * OUT_STRIDE <= SMEM_BYTES8, "epilogue staging fits in the allocation");
+static_assert(SMEM_BYTES8 <= 160 * 1024, "LDS budget of one CU");
+
+__device__ __forceinline__ void load_lds16(const void* src, char* lds_dst_wave_uniform) {
+  __builtin_amdgcn_global_load_lds((const CP_GLB_AS void*)src, (CP_LDS_AS void*)lds_dst_wave_uniform,
+                                   16, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8_t read_vt_frag(const char* a0, const char* a1) {
+  const shortx4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CP_LDS_AS shortx4_t*)a0);
+  const shortx4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((CP_LDS_AS shortx4_t*)a1);
+  typedef short shortx8_t __attribute__((ext_vector_type(8)));
+  const shortx8_t v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+template <typename TO, bool BAND>
+__global__ __launch_bounds__(NTHREADS) void prefill_mfma_dl_kernel(
+    Params p, const int2* __restrict__ tile_bounds) {
+  extern __shared__ __align__(16) char smem[];
+  char* const kbuf0 = smem;
+  char* const vbuf0 = smem + OFF_V8;
+  int32_t* const posbuf0 = (int32_t*)(smem + OFF_POS8);
+  int* const wg_scratch = (int*)(smem + OFF_SCRATCH8);
+  int4* const live = (int4*)(smem + OFF_LIVE8);
+
+  const int tid = threadIdx.x;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int n = lane & 31, g = lane >> 5;
+  const int row_block = gridDim.x - 1 - blockIdx.x;  // late (heavier) rows first
+  const int kvh = blockIdx.y;
+  const int split = blockIdx.z;
+
+  // ---- this lane's query row ----
+  const int64_t r = (int64_t)row_block * BM + wave * 32 + n;
+  const bool row_ok = r < p.rows;
+  const int64_t token = row_ok ? r / p.group : 0;
+  const int hg = row_ok ? (int)(r - token * p.group) : 0;
+  const int64_t row_lin = (token * p.n_kv_heads + kvh) * p.group + hg;
+  const int32_t qp = row_ok ? p.q_pos[token] : CP_POS_PAD_Q;
+  const int32_t ql = BAND && row_ok ? p.q_lo[token] : INT32_MIN;
+
+  bf16x8_t qf[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    uint4 t = make_uint4(0, 0, 0, 0);
+    if (row_ok) t = *(const uint4*)(p.q + row_lin * D + ks * 16 + g * 8);
+    qf[ks] = __builtin_bit_cast(bf16x8_t, t);
+  }
+
+  // ---- query position range of the wavefront and of the workgroup ----
+  int w_qmin = row_ok ? qp : INT32_MAX, w_qmax = qp;
+  const bool sees = row_ok && qp >= 0;
+  int w_lomin = BAND && sees ? ql : INT32_MAX, w_lomax = BAND && sees ? ql : INT32_MIN;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    w_qmin = min(w_qmin, __shfl_xor(w_qmin, o, 64));
+    w_qmax = max(w_qmax, __shfl_xor(w_qmax, o, 64));
+    if (BAND) {
+      w_lomin = min(w_lomin, __shfl_xor(w_lomin, o, 64));
+      w_lomax = max(w_lomax, __shfl_xor(w_lomax, o, 64));
+    }
+  }
+  if (lane == 0) {
+    wg_scratch[wave] = w_qmax;
+    if (BAND) wg_scratch[NWAVE + 1 + wave] = w_lomin;
+  }
+  __syncthreads();
+  int wg_qmax = INT32_MIN, wg_lomin = INT32_MAX;
+#pragma unroll
+  for (int w = 0; w < NWAVE; ++w) {
+    wg_qmax = max(wg_qmax, wg_scratch[w]);
+    if (BAND) wg_lomin = min(wg_lomin, wg_scratch[NWAVE + 1 + w]);
+  }
+  wg_qmax = __builtin_amdgcn_readfirstlane(wg_qmax);
+  w_qmin = __builtin_amdgcn_readfirstlane(w_qmin);
+  w_qmax = __builtin_amdgcn_readfirstlane(w_qmax);
+  if (BAND) {
+    wg_lomin = __builtin_amdgcn_readfirstlane(wg_lomin);
+    w_lomin = __builtin_amdgcn_readfirstlane(w_lomin);
+    w_lomax = __builtin_amdgcn_readfirstlane(w_lomax);
+  }
+
+  float m_run = -INFINITY;  // reference max of scaled scores (log2 domain)
+  float l_run = 0.f;        // running denominator over this lane's half of the keys
+  floatx16_t o_acc[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) o_acc[db][i] = 0.f;
+
+  // ---- tile loader: this wavefront brings rows wave*16 .. wave*16+15 of K and of V, four
+  // rows (1 KiB) per instruction; lane l covers row l/16 of the four, chunk position l%16 ----
+  const int64_t tok_stride = (int64_t)p.n_kv_heads * D;  // elements
+  const int l_row = lane >> 4, l_pos = lane & 15;
+  auto issue_tile = [&](int key0, int b) {
+    const int last = p.total_kv - 1;
+    const bool full = key0 + TILE <= p.total_kv;  // uniform
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row_in_tile = wave * 16 + i * 4 + l_row;
+      const int rsel = (i * 4 + l_row) & 15;  // row_in_tile & 15
+      // rows past the end of the shard are clamped to its last row (masked by their position)
+      const int64_t grow = full ? key0 + row_in_tile : min(key0 + row_in_tile, last);
+      const bf16_t* krow = p.k + grow * tok_stride + kvh * D;
+      const bf16_t* vrow = p.v + grow * tok_stride + kvh * D;
+      char* const kd = kbuf0 + b * KD_BYTES + (wave * 16 + i * 4) * ROW_BYTES;
+      char* const vd = vbuf0 + b * KD_BYTES + (wave * 16 + i * 4) * ROW_BYTES;
+      load_lds16(krow + (l_pos ^ rsel) * 8, kd);
+      load_lds16(vrow + (l_pos ^ ((l_row & 3) * 4)) * 8, vd);
+    }
+  };
+  // kv_pos of the tile goes through a register (the tail needs the pad value)
+  auto load_pos = [&](int key0) -> int32_t {
+    if (tid >= TILE) return 0;
+    const int key = key0 + tid;
+    return key < p.total_kv ? p.kv_pos[key] : CP_POS_PAD_KV;
+  };
+
+  // ---- fragment addressing ----
+  // K: lane (n, g) reads chunk 2*ks + g of rows n and n + 32 of a 64-key half
+  int k_chunk_off[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) k_chunk_off[ks] = ((2 * ks + g) ^ (n & 15)) * 16;
+  const int k_lane = n * ROW_BYTES;
+  // V: in its 16-lane group this lane addresses key j of four and 8 bytes (4 channels) q
+  const int grp = lane >> 4, vj = (lane & 15) >> 2, vq = lane & 3;
+  const int v_lane = ((grp >> 1) * 4 + vj) * ROW_BYTES + (grp & 1) * 32 + (vq >> 1) * 16 + (vq & 1) * 8;
+  int v_db_off[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) v_db_off[db] = (db ^ vj) * 64;
+
+  const int t_begin = split * p.tiles_per_split;
+  const int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
+  for (int c0 = t_begin; c0 < t_end; c0 += MAX_LIVE) {
+    __syncthreads();  // previous chunk (list, tile buffers) fully consumed
+    {
+      const int t = c0 + wave * 64 + lane;
+      int2 b = make_int2(0, 0);
+      bool lv = false;
+      if (t < t_end) {
+        b = tile_bounds[t];
+        lv = b.x <= wg_qmax && (!BAND || b.y >= wg_lomin);
+      }
+      const uint64_t mask = __builtin_amdgcn_ballot_w64(lv);
+      if (lane == 0) wg_scratch[wave] = __builtin_popcountll(mask);
+      __syncthreads();
+      int base = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < NWAVE; ++w) {
+        const int c = wg_scratch[w];
+        if (w < wave) base += c;
+        total += c;
+      }
+      if (lv)
+        live[base + __builtin_popcountll(mask & ((1ull << lane) - 1ull))] =
+            make_int4(t, b.x, b.y, 0);
+      if (tid == 0) wg_scratch[NWAVE] = total;
+    }
+    __syncthreads();
+    const int n_live = __builtin_amdgcn_readfirstlane(wg_scratch[NWAVE]);
+    if (n_live == 0) continue;
+
+    // prologue: first live tile into buffer 0
+    {
+      const int key0 = __builtin_amdgcn_readfirstlane(live[0].x) * TILE;
+      issue_tile(key0, 0);
+      const int32_t pos = load_pos(key0);
+      if (tid < TILE) posbuf0[tid] = pos;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): tile (and Q fragments) have landed
+    __syncthreads();
+
+    for (int it = 0; it < n_live; ++it) {
+      const int4 e = live[it];
+      const int tile = __builtin_amdgcn_readfirstlane(e.x);
+      const int bmin = __builtin_amdgcn_readfirstlane(e.y);
+      const int bmax = __builtin_amdgcn_readfirstlane(e.z);
+      const int buf = it & 1;
+      const bool has_next = it + 1 < n_live;
+      const bool two = tile * TILE + SUB < p.total_kv;
+      const bool wave_live = bmin <= w_qmax && (!BAND || bmax >= w_lomin);
+      const bool need_mask =
+          bmax > w_qmin || (tile + 1) * TILE > p.total_kv || (BAND && bmin < w_lomax);
+
+      // the next tile flies into the other buffer while this one is computed (every
+      // wavefront left that buffer behind at the barrier that ended the previous tile)
+      int32_t next_pos = 0;
+      if (has_next) {
+        const int next_key0 = __builtin_amdgcn_readfirstlane(live[it + 1].x) * TILE;
+        issue_tile(next_key0, buf ^ 1);
+        next_pos = load_pos(next_key0);
+      }
+
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        if (h == 1 && !two) break;
+        if (!wave_live) continue;
+        floatx16_t s[2];
+        bf16x8_t pb[4];
+        const char* kb = kbuf0 + buf * KD_BYTES + h * SUB * ROW_BYTES + k_lane;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[0][i] = s[1][i] = 0.f;
+        bf16x8_t ka[16];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          ka[2 * ks] = *(const bf16x8_t*)(kb + k_chunk_off[ks]);
+          ka[2 * ks + 1] = *(const bf16x8_t*)(kb + k_chunk_off[ks] + 32 * ROW_BYTES);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          s[0] = mfma32(ka[2 * ks], qf[ks], s[0]);
+          s[1] = mfma32(ka[2 * ks + 1], qf[ks], s[1]);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x100, kReadAhead, 0);
+#pragma unroll
+        for (int i = 0; i < 16 - kReadAhead; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kReadAhead, 0);
+
+        if (need_mask) {
+          const int32_t* pb32 = posbuf0 + buf * TILE + h * SUB + g * 4;
+#pragma unroll
+          for (int kb2 = 0; kb2 < 2; ++kb2)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              const int4 kp = *(const int4*)(pb32 + kb2 * 32 + q4 * 8);  // 4 consecutive keys
+              if (kp.x > qp || (BAND && kp.x < ql)) s[kb2][q4 * 4 + 0] = -INFINITY;
+              if (kp.y > qp || (BAND && kp.y < ql)) s[kb2][q4 * 4 + 1] = -INFINITY;
+              if (kp.z > qp || (BAND && kp.z < ql)) s[kb2][q4 * 4 + 2] = -INFINITY;
+              if (kp.w > qp || (BAND && kp.w < ql)) s[kb2][q4 * 4 + 3] = -INFINITY;
+            }
+        }
+
+        // online softmax in the log2 domain with a lazily raised reference maximum
+        float mx0 = fmaxf(s[0][0], s[1][0]), mx1 = fmaxf(s[0][1], s[1][1]);
+#pragma unroll
+        for (int i = 2; i < 16; i += 2) {
+          mx0 = fmaxf(fmaxf(mx0, s[0][i]), s[1][i]);
+          mx1 = fmaxf(fmaxf(mx1, s[0][i + 1]), s[1][i + 1]);
+        }
+        float mx = fmaxf(mx0, mx1);
+        mx = fmaxf(mx, xor32(mx));
+        const float m_step = mx * p.scale_log2;
+        const bool raise = m_step > m_run + kRescaleSlack;  // true on the first live step
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+          const float m_new = fmaxf(m_run, m_step);
+          const float alpha = __builtin_amdgcn_exp2f(m_run - (m_new == -INFINITY ? 0.f : m_new));
+          l_run *= alpha;
+          m_run = m_new;
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o_acc[db][i] *= alpha;
+        }
+        const float m_use = m_run == -INFINITY ? 0.f : m_run;
+        float lsum[2] = {0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const int kb2 = kk >> 1, i0 = (kk & 1) * 8;
+#pragma unroll
+          for (int jj = 0; jj < 8; jj += 2) {
+            const float e0 = __builtin_amdgcn_exp2f(fmaf(s[kb2][i0 + jj], p.scale_log2, -m_use));
+            const float e1 =
+                __builtin_amdgcn_exp2f(fmaf(s[kb2][i0 + jj + 1], p.scale_log2, -m_use));
+            lsum[(jj >> 1) & 1] += e0 + e1;
+            pb[kk][jj] = static_cast<bf16_t>(e0);
+            pb[kk][jj + 1] = static_cast<bf16_t>(e1);
+          }
+        }
+        l_run += lsum[0] + lsum[1];
+
+        // O^T += V^T P^T : 4 blocks of 32 channels, 4 steps of 16 keys. Slot jj of a lane's
+        // k-slice is key kk*16 + (jj/4)*8 + g*4 + jj%4, the order in which S^T hands over P.
+        const char* vb = vbuf0 + buf * KD_BYTES + h * SUB * ROW_BYTES + v_lane;
+        bf16x8_t va[16];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+          for (int db = 0; db < 4; ++db) {
+            const char* a0 = vb + v_db_off[db] + kk * 16 * ROW_BYTES;
+            va[kk * 4 + db] = read_vt_frag(a0, a0 + 8 * ROW_BYTES);
+          }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+          for (int db = 0; db < 4; ++db) o_acc[db] = mfma32(va[kk * 4 + db], pb[kk], o_acc[db]);
+        __builtin_amdgcn_sched_group_barrier(0x100, 2 * kReadAheadV, 0);
+#pragma unroll
+        for (int i = 0; i < 16 - kReadAheadV; ++i) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, kReadAheadV, 0);
+      }
+      if (has_next && tid < TILE) posbuf0[(buf ^ 1) * TILE + tid] = next_pos;
+      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's part of the next tile
+      __syncthreads();
+    }
+  }
+
+  // ---- epilogue ----
+  const float l_tot = l_run + xor32(l_run);
+  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  const float lse_val =
+      l_tot > 0.f ? (m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
+  const bool direct = p.n_splits == 1;
+  float* const lse_dst = direct ? p.lse : p.part_lse + (int64_t)split * p.rows_all_heads;
+  if (row_ok && g == 0) lse_dst[row_lin] = lse_val;
+
+  // Transpose through LDS (tile buffers are dead after the last barrier; each wavefront
+  // uses a private region).
+  char* const stage = smem + wave * 32 * OUT_STRIDE;
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int i4 = 0; i4 < 4; ++i4) {
+      const int d0 = db * 32 + i4 * 8 + g * 4;
+      floatx4_t w = {o_acc[db][i4 * 4 + 0] * inv, o_acc[db][i4 * 4 + 1] * inv,
+                     o_acc[db][i4 * 4 + 2] * inv, o_acc[db][i4 * 4 + 3] * inv};
+      *(floatx4_t*)(stage + n * OUT_STRIDE + d0 * 4) = w;
+    }
+  wave_lds_fence();
+  const int64_t r0 = (int64_t)row_block * BM + wave * 32;
+  if (direct && sizeof(TO) == 2) {
+    bf16_t* const o = (bf16_t*)p.out;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const int rr = pass * 4 + (lane >> 4), c = (lane & 15) * 8;
+      const int64_t rl = __shfl(row_lin, rr, 64);
+      const floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      const floatx4_t b = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4 + 16);
+      bf16x8_t w;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        w[x] = static_cast<bf16_t>(a[x]);
+        w[4 + x] = static_cast<bf16_t>(b[x]);
+      }
+      if (r0 + rr < p.rows) *(bf16x8_t*)(o + rl * D + c) = w;
+    }
+  } else {
+    float* const o =
+        direct ? (float*)p.out : p.part_out + (int64_t)split * p.rows_all_heads * D;
+#pragma unroll
+    for (int pass = 0; pass < 16; ++pass) {
+      const int rr = pass * 2 + (lane >> 5), c = (lane & 31) * 4;
+      const int64_t rl = __shfl(row_lin, rr, 64);
+      const floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      if (r0 + rr < p.rows) *(floatx4_t*)(o + rl * D + c) = a;
+    }
+  }
+}
+
 struct Plan {
   int n_tiles, n_row_blocks, n_splits, tiles_per_split;
   size_t bounds_bytes, part_out_bytes, part_lse_bytes;
@@ -631,14 +1015,23 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
 
   const dim3 grid(pl.n_row_blocks, s.n_kv_heads, pl.n_splits);
   const bool direct_bf16 = pl.n_splits == 1 && out_dtype == CP_BF16;
+#ifdef CP_PREFILL_STAGED
   auto kern = q_lo != nullptr
                   ? (direct_bf16 ? prefill_mfma_kernel<bf16_t, true> : prefill_mfma_kernel<float, true>)
                   : (direct_bf16 ? prefill_mfma_kernel<bf16_t, false>
                                  : prefill_mfma_kernel<float, false>);
+  constexpr int kSmem = SMEM_BYTES;
+#else
+  auto kern = q_lo != nullptr ? (direct_bf16 ? prefill_mfma_dl_kernel<bf16_t, true>
+                                             : prefill_mfma_dl_kernel<float, true>)
+                              : (direct_bf16 ? prefill_mfma_dl_kernel<bf16_t, false>
+                                             : prefill_mfma_dl_kernel<float, false>);
+  constexpr int kSmem = SMEM_BYTES8;
+#endif
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                          SMEM_BYTES) != hipSuccess)
+                          kSmem) != hipSuccess)
     return CP_ERR_LAUNCH;
-  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), SMEM_BYTES, stream, p, p.bounds);
+  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), kSmem, stream, p, p.bounds);
   if (check_launch() != CP_OK) return CP_ERR_LAUNCH;
 
   if (pl.n_splits > 1)
