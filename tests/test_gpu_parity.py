@@ -183,6 +183,37 @@ def test_mfma_partial_softmax_scale_and_short_rows(oracle):
                                atol=1e-6)
 
 
+@pytest.mark.parametrize("causal,tq", [(False, 96), (True, 96), (False, 2048)])
+def test_mfma_partial_score_spikes(oracle, causal, tq):
+    # Keys whose score lies far above everything seen before them (45 and then 80 log2 units
+    # above the running reference), and one far below: the kernel's softmax keeps a standing
+    # reference without looking at block maxima and must notice such blocks and redo them.
+    # The spikes sit in the second and third 32-key block of their 128-key tile, so a
+    # reference exists when they arrive, also where the KV axis is split per tile (tq = 96);
+    # tq = 2048 is the unsplit walk over all tiles.
+    t = 600
+    u, _ = randn(41, (128,))
+    noise, _ = randn(42, (tq, 16, 128))
+    q = (u.float()[None, None, :] + 0.1 * noise.float()).to(torch.bfloat16)
+    k, _ = randn(43, (t, 1, 128))
+    v, v64 = randn(44, (t, 1, 128))
+    k = k.clone()
+    k[182, 0] = (3.0 * u.float()).to(torch.bfloat16)
+    k[183, 0] = (-6.0 * u.float()).to(torch.bfloat16)
+    k[464, 0] = (5.0 * u.float()).to(torch.bfloat16)
+    q64, k64 = W.to_f64(q), W.to_f64(k)
+    kp = np.arange(t)
+    qp = np.linspace(5, t - 1, tq).astype(np.int64) if causal else np.full(tq, 10**6)
+    ref = oracle.attn(q64, k64, v64, qp, kp)
+    o, l = gpu_partial(q, k, v, qp, kp, out_dtype=torch.float32)
+    check(o, l, *ref)
+    sees_big = qp >= 464
+    assert sees_big.any()
+    # rows that see the largest spike are that key's value row, to bf16 rounding of P
+    np.testing.assert_allclose(o[sees_big].cpu().double().numpy(),
+                               np.broadcast_to(v64[464], (int(sees_big.sum()), 16, 128)), atol=1e-2)
+
+
 @pytest.mark.parametrize("n,t", [(4, 2048), (3, 1000)])
 def test_mfma_load_balanced_partials_and_merge(oracle, n, t):
     q, q64 = randn(41, (t, 16, 128))
