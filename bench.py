@@ -279,6 +279,28 @@ def selector_table(c_flops: float):
 PROBE_COPY_BYTES = 1 << 28
 
 
+def mfma_rate_probe(iters: int = 20000, reps: int = 3):
+    """What a bare loop of bf16 MFMAs sustains on this part, for zero and for N(0,1) operands
+    (the second draws more power and settles at a lower clock): context for roofline.frac."""
+    n_wg = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.empty(n_wg * 512, dtype=torch.float32, device="cuda")
+    n_el = B.CP_PROBE_OPERAND_BYTES // 2
+    out = {}
+    for name, ops in (("zeros", torch.zeros(n_el, dtype=torch.bfloat16, device="cuda")),
+                      ("normal", W.normal(77, (n_el,), "bf16", "cuda"))):
+        best = 0.0
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            flop = B.cp_probe_mfma_rate(ops, iters, n_wg, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        out["tflops_%s_operands" % name] = round(best, 1)
+    out["workgroups"] = n_wg
+    return out
+
+
 def pmc_probe(ring):
     """The work the counter runs profile: a streaming kernel that reads and writes
     PROBE_COPY_BYTES (the scale reference), one pass-KV ring pass, one decode pass."""
@@ -376,6 +398,7 @@ def main():
             ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
              "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"])
         result["aux"]["selector"] = selector_table(tflops * 1e12)
+        result["aux"]["mfma_rate_probe"] = mfma_rate_probe()
     print(json.dumps(result))
 
 

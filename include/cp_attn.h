@@ -274,6 +274,21 @@ typedef struct {
 int cp_select_order(const cp_select_params* params, int64_t t_new, int64_t p_cached,
                     int32_t rule, int32_t* order_out);
 
+/*
+ * Measurement support (not a step of the paper's method): sustained rate of the matrix
+ * pipe. Launches one workgroup of 8 wavefronts per entry of `n_workgroups`, each issuing
+ * iters * 16 independent v_mfma_f32_32x32x16_bf16 on the operands found in
+ * `operands` (device, at least CP_PROBE_OPERAND_BYTES bytes of bf16, read once into
+ * registers), and writes one float per thread to `sink` (device, n_workgroups * 512
+ * floats). *flop_out (host) receives the floating-point operations of the launch. The
+ * rate depends on the operand VALUES (zeros versus random data draw different power),
+ * which is why the caller supplies them. Asynchronous on hip_stream.
+ * Errors: CP_ERR_NULL, CP_ERR_SHAPE (iters < 1 or n_workgroups < 1), CP_ERR_LAUNCH.
+ */
+#define CP_PROBE_OPERAND_BYTES 65536
+int cp_probe_mfma_rate(const void* operands, int32_t iters, int32_t n_workgroups, void* sink,
+                       double* flop_out, void* hip_stream);
+
 /* Static description of a cp_status. Never NULL. */
 const char* cp_strerror(int status);
 

@@ -25,8 +25,10 @@ CP_MAX_PARTS = 64
 EXPORTS = [
     "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_decode",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
-    "cp_ring_workspace_bytes", "cp_select_order", "cp_strerror", "cp_version",
+    "cp_ring_workspace_bytes", "cp_select_order", "cp_probe_mfma_rate", "cp_strerror",
+    "cp_version",
 ]
+CP_PROBE_OPERAND_BYTES = 65536
 
 _vp = ctypes.c_void_p
 _i32, _i64, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
@@ -109,6 +111,8 @@ def load() -> ctypes.CDLL:
     lib.cp_select_order.restype = ctypes.c_int
     lib.cp_select_order.argtypes = [ctypes.POINTER(cp_select_params), _i64, _i64, _i32,
                                     ctypes.POINTER(_i32)]
+    lib.cp_probe_mfma_rate.restype = ctypes.c_int
+    lib.cp_probe_mfma_rate.argtypes = [_vp, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
     _lib = lib
     return lib
 
@@ -157,6 +161,17 @@ def make_shape(dtype: int, head_dim: int, n_q_heads: int, n_kv_heads: int, total
 
 def cp_version() -> int:
     return int(load().cp_version())
+
+
+def cp_probe_mfma_rate(operands: torch.Tensor, iters: int, n_workgroups: int,
+                       sink: torch.Tensor, stream=None) -> float:
+    """Launch the matrix-pipe rate probe; returns the launch's floating-point operations."""
+    assert operands.numel() * operands.element_size() >= CP_PROBE_OPERAND_BYTES
+    assert sink.numel() >= n_workgroups * 512 and sink.dtype == torch.float32
+    flop = ctypes.c_double(0.0)
+    _check(load().cp_probe_mfma_rate(_ptr(operands), int(iters), int(n_workgroups), _ptr(sink),
+                                     ctypes.byref(flop), _stream(stream)), "cp_probe_mfma_rate")
+    return flop.value
 
 
 def cp_shard_positions(total: int, n_ranks: int, rank: int, offset: int = 0) -> np.ndarray:

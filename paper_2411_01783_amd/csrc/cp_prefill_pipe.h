@@ -133,7 +133,8 @@ template <int BLK, bool BAND, typename Hook>
 __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
                                           const uint32_t (&kaddr)[8], const uint32_t (&vaddr)[4],
                                           uint32_t paddr, int32_t qp, int32_t ql,
-                                          float scale_log2, bool need_mask, Hook hook) {
+                                          float scale_log2, bool need_mask, bool& have_ref,
+                                          Hook hook) {
   constexpr int CUR = BLK & 1, NXT = CUR ^ 1;
   constexpr int KOFF = ((BLK + 1) & 3) * BLK_BYTES;
   constexpr int VOFF = BLK * BLK_BYTES;
@@ -143,6 +144,8 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
   constexpr int kBound[15] = {0, 1, 2, 3, 5, 6, 7, 8, 9, 10, 11, 13, 14, 15, 16};
 
   floatx16_t& s = R.s[CUR];
+  float dm[4] = {R.l_run, R.l_run + 1.f, R.l_run + 2.f, R.l_run + 3.f}; (void)dm;
+  unsigned dacc = 0; (void)dacc;
   float e[16];
   float m_use = 0.f, alpha = 1.f;
   float lsum0 = 0.f, lsum1 = 0.f;
@@ -175,7 +178,11 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
       unsigned pk = pack_bf16(e[v - 1], e[v]);
       pin(pk);
       pin(lsum1);
+#ifdef CP_X_DUMMYOUT
+      dacc ^= pk;
+#else
       R.pb[CUR][v >> 3][(v & 7) >> 1] = pk;
+#endif
     } else {
       lsum0 += e[v];
       pin(lsum0);
@@ -185,8 +192,8 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
   auto valu = [&](auto jc) __attribute__((always_inline)) {
     constexpr int J = decltype(jc)::value;
     if constexpr (J == 0) {
-      const bool full = need_mask || __builtin_amdgcn_ballot_w64(R.m_run == -INFINITY) != 0;
-      if (full) {  // wave-uniform
+      const bool full = need_mask | !have_ref;  // scalar flags: one branch on the hot path
+      if (__builtin_expect(full, 0)) {  // wave-uniform, rare: laid out off the hot path
         if (need_mask) {
           // Masked tiles are the few on the diagonal: their kv_pos reads are simply waited
           // for (which also completes every older LDS read, so the counted waits hold).
@@ -210,15 +217,25 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
         R.l_run *= alpha;
         R.m_run = m_new;
         m_use = m_new == -INFINITY ? 0.f : m_new;
+        have_ref = __builtin_amdgcn_ballot_w64(m_new == -INFINITY) == 0;
       } else {
         m_use = R.m_run;
       }
       pin(m_use);
     } else {
+#ifdef CP_X_NOVALU
+      if (true) return;
+#endif
       if constexpr (J <= 14) {
 #pragma unroll
         for (int v = kBound[J - 1]; v < kBound[J]; ++v) {
+#if defined(CP_X_DUMMYIN)
+          e[v] = __builtin_amdgcn_exp2f(fmaf(dm[v & 3], scale_log2, -m_use));
+#elif defined(CP_X_NOEXP)
+          e[v] = fmaf(s[v], scale_log2, -m_use) * 1e-30f;
+#else
           e[v] = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -m_use));
+#endif
           pin(e[v]);
         }
       }
@@ -237,7 +254,9 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
     lgkm_wait<14 - 2 * M + M>(R.vf[M]);
     R.o[M & 3] = mfma32(__builtin_bit_cast(bf16x8_t, R.vf[M]),
                         __builtin_bit_cast(bf16x8_t, R.pb[NXT][M >> 2]), R.o[M & 3]);
+#ifndef CP_X_NOLDS
     R.kf[M] = lds_read_b128<KOFF>(kaddr[M]);
+#endif
     hook(IntC<M>{});
     valu(IntC<M>{});
     __builtin_amdgcn_sched_barrier(0);
@@ -258,7 +277,9 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
     } else {
       R.s[NXT] = mfma32(__builtin_bit_cast(bf16x8_t, R.kf[M]), qf[M], R.s[NXT]);
     }
+#ifndef CP_X_NOLDS
     R.vf[M] = lds_read_vt_frag<VOFF + (M >> 2) * 16 * ROW_BYTES>(vaddr[M & 3]);
+#endif
     hook(IntC<8 + M>{});
     valu(IntC<8 + M>{});
     __builtin_amdgcn_sched_barrier(0);
@@ -269,7 +290,7 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
   // A block of the fast form whose exponentials ran away from the reference (rare): redo
   // its softmax in the full form. No row's sum can pass the test with an infinity or a NaN.
   float blk = lsum0 + lsum1;
-  if (__builtin_amdgcn_ballot_w64(!(blk <= kOverflowSum)) != 0) {
+  if (__builtin_expect(__builtin_amdgcn_ballot_w64(!(blk <= kOverflowSum)) != 0, 0)) {
     const float m_step = block_max() * scale_log2;
     const float m_new = fmaxf(R.m_run, m_step);
     m_use = m_new == -INFINITY ? 0.f : m_new;
@@ -287,8 +308,11 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
     blk = lsum0 + lsum1;
   }
   R.l_run += blk;
+#ifdef CP_X_DUMMYOUT
+  R.l_run += (float)(dacc & 1);
+#endif
   // rows whose reference maximum moved: bring O to the new reference (rare)
-  if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+  if (__builtin_expect(__builtin_amdgcn_ballot_w64(raise) != 0, 0)) {
 #pragma unroll
     for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -300,7 +324,7 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
 // BAND: packed batch. Positions are shifted per sequence and a query also has a lower bound
 // q_lo (the shift of its sequence): visible iff q_lo <= kv_pos <= q_pos.
 template <typename TO, bool BAND>
-__global__ __launch_bounds__(NTHREADS) void prefill_mfma_pipe_kernel(
+__global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     Params p, const int2* __restrict__ tile_bounds) {
   extern __shared__ __align__(16) char smem[];
   char* const kbuf0 = smem;
@@ -369,6 +393,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_pipe_kernel(
     w_lomax = __builtin_amdgcn_readfirstlane(w_lomax);
   }
 
+  bool have_ref = false;  // every row of the wavefront has a finite reference maximum
   PipeRegs R;
   R.m_run = -INFINITY;  // reference max of scaled scores (log2 domain)
   R.l_run = 0.f;        // running denominator over this lane's half of the keys
@@ -381,6 +406,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_pipe_kernel(
   // rows (1 KiB) per instruction and tile; lane l covers row l/16 of the four, chunk position
   // l%16. Part I of a tile is one such instruction for K and one for V. `rows_valid` clamps
   // rows past the end of the shard to its last row (they are masked by their position).
+  int first_key0 = 0; (void)first_key0;
   const uint32_t stride_b = (uint32_t)p.n_kv_heads * ROW_BYTES;  // bytes between tokens
   const int l_row = lane >> 4, l_pos = lane & 15;
   const uint32_t v_chunk = (l_pos ^ ((l_row & 3) * 4)) * 16;
@@ -388,6 +414,9 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_pipe_kernel(
   const char* const v_head = (const char*)p.v + (int64_t)kvh * ROW_BYTES;
   auto issue_part = [&](auto ic, int key0, int b) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value;
+#ifdef CP_X_NODMA
+    if (b >= 0 && key0 != first_key0) return;
+#endif
     const int row = wave * 16 + I * 4 + l_row;
     const uint32_t row_c = (uint32_t)min(row, total_kv - 1 - key0);
     const uint32_t roff = __umul24(row_c, stride_b);
@@ -461,6 +490,9 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_pipe_kernel(
     // ---- prologue: tile 0 into buffer 0, Q stage of block 0 ----
     int32_t next_pos = 0;
     bool need_mask, next_mask = false;
+#ifdef CP_X_NODMA
+    first_key0 = __builtin_amdgcn_readfirstlane(live[0].x) * TILE;
+#endif
     int next_key0 = 0;
     auto read_entry = [&](int idx, int& key0, bool& mask_it) {
       const int4 e = live[idx < n_live ? idx : n_live - 1];
@@ -510,22 +542,22 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_pipe_kernel(
       // The next tile is requested during the first two steps, one part (a K and a V
       // instruction per wavefront) at a time: a burst of all eight fills the memory pipeline's
       // queue and stalls every wavefront behind it.
-      pipe_body<0, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask,
+      pipe_body<0, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref,
                          [&](auto mc) __attribute__((always_inline)) {
                            constexpr int M = decltype(mc)::value;
-                           if (M == 1 && has_next) issue_part(IntC<0>{}, next_key0, nb);
-                           if (M == 9 && has_next) issue_part(IntC<1>{}, next_key0, nb);
+                           if (M == 1 && __builtin_expect(has_next, 1)) issue_part(IntC<0>{}, next_key0, nb);
+                           if (M == 9 && __builtin_expect(has_next, 1)) issue_part(IntC<1>{}, next_key0, nb);
                          });
-      pipe_body<1, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask,
+      pipe_body<1, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref,
                          [&](auto mc) __attribute__((always_inline)) {
                            constexpr int M = decltype(mc)::value;
-                           if (M == 1 && has_next) issue_part(IntC<2>{}, next_key0, nb);
-                           if (M == 9 && has_next) {
+                           if (M == 1 && __builtin_expect(has_next, 1)) issue_part(IntC<2>{}, next_key0, nb);
+                           if (M == 9 && __builtin_expect(has_next, 1)) {
                              issue_part(IntC<3>{}, next_key0, nb);
                              next_pos = load_pos(next_key0);
                            }
                          });
-      pipe_body<2, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, no_hook);
+      pipe_body<2, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref, no_hook);
       // barrier Y: the next tile has landed in every wavefront
       CP_STAMP(0);
       __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -534,15 +566,19 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_pipe_kernel(
       const bool cur_mask = need_mask;
       need_mask = next_mask;
       read_entry(it + 2, next_key0, next_mask);  // no direct-to-LDS load is in flight here
+#ifndef CP_X_NOBAR
       __syncthreads();
+#endif
       CP_STAMP(2);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) kaddr[ks] ^= KD_BYTES;  // K of the next tile from here on
-      pipe_body<3, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, cur_mask, no_hook);
+      pipe_body<3, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, cur_mask, have_ref, no_hook);
       // barrier X: every LDS read of this tile has completed; its buffers may be refilled
       __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
       CP_STAMP(3);
+#ifndef CP_X_NOBAR
       __syncthreads();
+#endif
       CP_STAMP(4);
 #pragma unroll
       for (int db = 0; db < 4; ++db) vaddr[db] ^= KD_BYTES;

@@ -30,6 +30,17 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_probe_rejects_bad_arguments_before_any_launch(lib):
+    import ctypes
+    flop = ctypes.c_double(0.0)
+    one = ctypes.c_void_p(256)  # never dereferenced: every call below fails validation first
+    assert lib.cp_probe_mfma_rate(None, 1, 1, one, ctypes.byref(flop), None) == -1  # CP_ERR_NULL
+    assert lib.cp_probe_mfma_rate(one, 1, 1, None, ctypes.byref(flop), None) == -1
+    assert lib.cp_probe_mfma_rate(one, 1, 1, one, None, None) == -1
+    assert lib.cp_probe_mfma_rate(one, 0, 1, one, ctypes.byref(flop), None) == -2  # CP_ERR_SHAPE
+    assert lib.cp_probe_mfma_rate(one, 1, 0, one, ctypes.byref(flop), None) == -2
+
+
 def test_version_and_strerror(lib):
     assert B.cp_version() >= 100
     assert B.strerror(0) == "ok"
