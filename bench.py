@@ -57,7 +57,9 @@ def build_prefill(w: W.Workload):
     vs = [v[i].contiguous() for i in idx]
     del q
     ps = [_i32(p) for p in pos]
-    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
+    # the ring driver alternates a rank's calls between the current stream and this one
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32,
+                  aux_stream=torch.cuda.Stream())
     return dict(ring=ring, pos=pos, qs=qs, ks=ks, vs=vs, ps=ps, k_full=k, v_full=v)
 
 

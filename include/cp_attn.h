@@ -209,6 +209,19 @@ typedef struct {
   int32_t batch;                       /* sequences packed in every rank's KV */
   const int32_t* const* cu_seqlens_kv; /* (host) -> (device) int32 [batch+1] per rank */
   const int32_t* const* bid;           /* (host) -> (device) int32 [n_q[k]] per rank */
+  /*
+   * Optional second HIP stream (default priority), or NULL. When given, the prefill
+   * drivers issue the N partial-attention calls of one rank alternately on `stream` and
+   * on aux_stream, so that the tail of one call (its last workgroups, its output writes)
+   * overlaps the start of the next; both are joined before the rank's merge, and
+   * everything the driver enqueues is ordered after prior work on `stream` and before
+   * later work on it. The calls of one rank write different partial slots and only read
+   * their inputs, so their order does not matter. Ignored (single stream) by the decode
+   * driver and whenever a call needs per-call scratch (split KV walks of short query
+   * shards), which consecutive calls share. Two events are created and destroyed per
+   * driver call; no device memory is allocated.
+   */
+  void* aux_stream;
 } cp_ring_desc;
 
 /*

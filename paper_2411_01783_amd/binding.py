@@ -52,7 +52,8 @@ class cp_ring_desc(ctypes.Structure):
                 ("keep_partials", _i32), ("reserved", _i32),
                 ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t),
                 ("batch", _i32),
-                ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp))]
+                ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp)),
+                ("aux_stream", _vp)]
 
 
 class cp_select_params(ctypes.Structure):
@@ -294,7 +295,7 @@ class Ring:
                  out_dtype: Optional[torch.dtype] = None, part_dtype: torch.dtype = torch.float32,
                  keep_partials: bool = False, softmax_scale: float = 0.0,
                  cu_seqlens_kv: Optional[List[torch.Tensor]] = None,
-                 bid: Optional[List[torch.Tensor]] = None):
+                 bid: Optional[List[torch.Tensor]] = None, aux_stream=None):
         n = len(q)
         self.n = n
         self.decode = cu_seqlens_kv is not None
@@ -334,6 +335,9 @@ class Ring:
             dsc.batch = cu_seqlens_kv[0].numel() - 1
             dsc.cu_seqlens_kv = ctypes.cast(self._cu, ctypes.POINTER(_vp))
             dsc.bid = ctypes.cast(self._bid, ctypes.POINTER(_vp))
+        self.aux_stream = aux_stream  # keep alive
+        if aux_stream is not None:
+            dsc.aux_stream = aux_stream.cuda_stream
         self.desc = dsc
         nbytes = int(load().cp_ring_workspace_bytes(ctypes.byref(dsc), 1 if self.decode else 0))
         self.workspace = _workspace(nbytes, dev)

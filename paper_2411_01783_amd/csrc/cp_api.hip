@@ -279,6 +279,9 @@ RingSlots make_slots(const cp_ring_desc* d) {
 
 struct RingWork {
   bool use_bounds = false;
+  bool dual = false;          // alternate the calls of a rank between two streams
+  hipStream_t aux = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
   size_t bounds_off[CP_MAX_PARTS] = {};
   char* call_ws = nullptr;
   size_t call_ws_bytes = 0;
@@ -302,6 +305,54 @@ int ring_prepare(const cp_ring_desc* d, bool decode, hipStream_t st, RingWork& w
   }
   w.call_ws = (char*)d->workspace + off;
   w.call_ws_bytes = d->workspace_bytes >= off ? d->workspace_bytes - off : 0;
+  // Two streams only when no call touches the shared per-call scratch.
+  if (d->aux_stream != nullptr && !decode && w.use_bounds) {
+    bool scratch = false;
+    for (int a = 0; a < d->n_ranks && !scratch; ++a)
+      for (int b = 0; b < d->n_ranks && !scratch; ++b) {
+        const cp_shape s = ring_shape(d, a, b, false);
+        scratch = prefill_mfma_workspace_bytes(s) > kv_tile_bounds_bytes(s.total_kv);
+      }
+    if (!scratch) {
+      if (hipEventCreateWithFlags(&w.fork, hipEventDisableTiming) != hipSuccess) return CP_ERR_LAUNCH;
+      if (hipEventCreateWithFlags(&w.join, hipEventDisableTiming) != hipSuccess) {
+        (void)hipEventDestroy(w.fork);
+        return CP_ERR_LAUNCH;
+      }
+      w.dual = true;
+      w.aux = (hipStream_t)d->aux_stream;
+    }
+  }
+  return CP_OK;
+}
+
+void ring_finish(RingWork& w) {
+  if (w.dual) {
+    (void)hipEventDestroy(w.fork);
+    (void)hipEventDestroy(w.join);
+    w.dual = false;
+  }
+}
+
+// The N partial calls of one rank: `call(j, stream)` issues step j. With two streams the
+// aux stream first waits for everything enqueued on `st` so far (the previous rank's merge
+// still reads the slots), and `st` waits for the aux stream before the caller merges.
+template <typename Call>
+int ring_rank_steps(const RingWork& w, int n, hipStream_t st, Call call) {
+  if (w.dual) {
+    if (hipEventRecord(w.fork, st) != hipSuccess ||
+        hipStreamWaitEvent(w.aux, w.fork, 0) != hipSuccess)
+      return CP_ERR_LAUNCH;
+  }
+  for (int j = 0; j < n; ++j) {
+    const int rc = call(j, (w.dual && (j & 1)) ? w.aux : st);
+    if (rc != CP_OK) return rc;
+  }
+  if (w.dual) {
+    if (hipEventRecord(w.join, w.aux) != hipSuccess ||
+        hipStreamWaitEvent(st, w.join, 0) != hipSuccess)
+      return CP_ERR_LAUNCH;
+  }
   return CP_OK;
 }
 
@@ -350,17 +401,16 @@ int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
   rc = ring_prepare(d, false, st, w);
   if (rc != CP_OK) return rc;
   // Algorithm 2 as seen from each rank k in turn: N ring steps, then a local merge.
-  for (int k = 0; k < n; ++k) {
+  for (int k = 0; k < n && rc == CP_OK; ++k) {
     const int64_t base = d->keep_partials ? (int64_t)k * n : 0;
-    for (int j = 0; j < n; ++j) {
+    rc = ring_rank_steps(w, n, st, [&](int j, hipStream_t sj) {
       const int s = ((k - j) % n + n) % n;  // origin rank of the KV held at step j
-      rc = ring_partial(d, w, false, k, s, slots.out(base + s), slots.lse(base + s), st);
-      if (rc != CP_OK) return rc;
-    }
-    rc = ring_merge(d, slots, k, base, st);
-    if (rc != CP_OK) return rc;
+      return ring_partial(d, w, false, k, s, slots.out(base + s), slots.lse(base + s), sj);
+    });
+    if (rc == CP_OK) rc = ring_merge(d, slots, k, base, st);
   }
-  return CP_OK;
+  ring_finish(w);
+  return rc;
 }
 
 static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
@@ -375,32 +425,28 @@ static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
   if (d->keep_partials) {
     // Algorithms 3 / 4 in ring order: at step j rank k holds the queries of rank
     // s = (k - j) mod N. Writing the result to slot [s][k] is the permute + All2All.
-    for (int j = 0; j < n; ++j)
-      for (int k = 0; k < n; ++k) {
+    for (int j = 0; j < n && rc == CP_OK; ++j)
+      for (int k = 0; k < n && rc == CP_OK; ++k) {
         const int s = ((k - j) % n + n) % n;
         rc = ring_partial(d, w, decode, s, k, slots.out((int64_t)s * n + k),
                           slots.lse((int64_t)s * n + k), st);
-        if (rc != CP_OK) return rc;
       }
-    for (int s = 0; s < n; ++s) {
-      rc = ring_merge(d, slots, s, (int64_t)s * n, st);
-      if (rc != CP_OK) return rc;
-    }
-    return CP_OK;
+    for (int s = 0; s < n && rc == CP_OK; ++s) rc = ring_merge(d, slots, s, (int64_t)s * n, st);
+    ring_finish(w);
+    return rc;
   }
   // With N reusable slots the same N*N calls are issued grouped by source rank s
   // (for each s the holders k = s, s+1, ... in ring order), so that the N partials of
   // one source are complete, and can be merged, before the slots are reused.
-  for (int s = 0; s < n; ++s) {
-    for (int j = 0; j < n; ++j) {
+  for (int s = 0; s < n && rc == CP_OK; ++s) {
+    rc = ring_rank_steps(w, n, st, [&](int j, hipStream_t sj) {
       const int k = (s + j) % n;
-      rc = ring_partial(d, w, decode, s, k, slots.out(k), slots.lse(k), st);
-      if (rc != CP_OK) return rc;
-    }
-    rc = ring_merge(d, slots, s, 0, st);
-    if (rc != CP_OK) return rc;
+      return ring_partial(d, w, decode, s, k, slots.out(k), slots.lse(k), sj);
+    });
+    if (rc == CP_OK) rc = ring_merge(d, slots, s, 0, st);
   }
-  return CP_OK;
+  ring_finish(w);
+  return rc;
 }
 
 int cp_ring_passq(const cp_ring_desc* d, void* stream) { return ring_passq_common(d, false, stream); }

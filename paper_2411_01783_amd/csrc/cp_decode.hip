@@ -326,7 +326,10 @@ int plan_splits(const cp_shape& s) {
   const int64_t wg_per_split = std::max<int64_t>(1, s.total_q * s.n_kv_heads);
   const int64_t avg_len = s.batch > 0 ? s.total_kv / s.batch : 0;
   int splits = 1;
-  while (splits < CP_MAX_PARTS && wg_per_split * splits * 2 <= 512 &&
+#ifndef CP_DEC_TARGET_WGS
+#define CP_DEC_TARGET_WGS 512
+#endif
+  while (splits < CP_MAX_PARTS && wg_per_split * splits * 2 <= CP_DEC_TARGET_WGS &&
          (int64_t)splits * 2 * 128 <= avg_len)
     splits *= 2;
   return splits;

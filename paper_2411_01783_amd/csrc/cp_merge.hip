@@ -89,7 +89,29 @@ __global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float*
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
     float den = 0.f;
-    if (lmax != -INFINITY) {
+    if constexpr (STRIDED && NP > 0 && NP <= 16) {
+      // Split-KV scratch of one call: few rows, so the kernel is bound by latency, not by
+      // bandwidth. Every row of the scratch is written (finite zeros when empty), so all NP
+      // loads are issued at once, next to the LSE loads, and the arithmetic is branch-free
+      // (a branch on the weights would pull the loads behind the wait for the LSE values).
+      float xs[NP][VEC];
+#pragma unroll
+      for (int s = 0; s < NP; ++s)
+        load_vec<TP, VEC>((const TP*)(parts_out + (s * part_stride_rows + row) * head_dim) + col,
+                          xs[s]);
+      __builtin_amdgcn_sched_barrier(0);  // keep the NP loads together, ahead of the arithmetic
+      const bool any = lmax != -INFINITY;
+#pragma unroll
+      for (int s = 0; s < NP; ++s) {
+        const float w = any ? __expf(lv[s] - lmax) : 0.f;  // exp(-inf) = 0 for empty partials
+        den += w;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, xs[s][i], acc[i]);
+      }
+      const float inv = any ? 1.f / den : 0.f;
+#pragma unroll
+      for (int i = 0; i < VEC; ++i) acc[i] *= inv;
+    } else if (lmax != -INFINITY) {
 #pragma unroll
       for (int s = 0; s < n_parts; ++s) {
         const float x = NP > 0 ? lv[NP > 0 ? s : 0]
@@ -123,13 +145,19 @@ int launch_np(const MergePtrs& ptrs, const float* parts_out, const float* parts_
               hipStream_t stream) {
   const int64_t n_vec = rows * (head_dim / VEC);
   if (n_vec == 0) return CP_OK;
-  int64_t blocks = (n_vec + 255) / 256;
+  // Small merges (the split partials of a decode step) are latency-bound: one wavefront per
+  // workgroup spreads them over every CU instead of a quarter of them.
+#ifndef CP_MERGE_SMALL_VEC
+#define CP_MERGE_SMALL_VEC (256 * 256)
+#endif
+  const int threads = n_vec <= CP_MERGE_SMALL_VEC ? 64 : 256;
+  int64_t blocks = (n_vec + threads - 1) / threads;
   const int64_t cap = 256 * 32;  // grid-stride beyond 32 workgroups per CU
   if (blocks > cap) blocks = cap;
 #define CP_MERGE_LAUNCH(NP)                                                                   \
   hipLaunchKernelGGL((merge_kernel<TP, TO, VEC, NP, STRIDED>), dim3((unsigned)blocks),        \
-                     dim3(256), 0, stream, ptrs, parts_out, parts_lse, stride, n_parts, rows, \
-                     head_dim, (TO*)out, lse_out)
+                     dim3(threads), 0, stream, ptrs, parts_out, parts_lse, stride, n_parts,   \
+                     rows, head_dim, (TO*)out, lse_out)
   switch (n_parts) {
     case 2: CP_MERGE_LAUNCH(2); break;
     case 4: CP_MERGE_LAUNCH(4); break;

@@ -218,4 +218,7 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
 extern "C" int cp_debug_read(void* dst) {
   return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(cp::cp_dbg), sizeof(cp::cp_dbg));
 }
+extern "C" int cp_debug_read2(void* dst) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(cp::cp_dbg2), sizeof(cp::cp_dbg2));
+}
 #endif

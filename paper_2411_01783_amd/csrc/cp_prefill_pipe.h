@@ -110,6 +110,7 @@ struct PipeRegs {
 
 #ifdef CP_PIPE_STAMPS
 __device__ unsigned long long cp_dbg[1024 * 8 * 8];
+__device__ unsigned long long cp_dbg2[1024 * 8 * 4];
 #define CP_STAMP(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st[i] += t_ - t_prev; t_prev = t_; } while (0)
 #else
 #define CP_STAMP(i) do { } while (0)
@@ -334,6 +335,10 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   int4* const live = (int4*)(smem + OFF_LIVE8);
   const uint32_t smem_lds = (uint32_t)(size_t)(CP_LDS_AS char*)smem;
 
+#ifdef CP_PIPE_STAMPS
+  const unsigned long long t_entry = __builtin_readcyclecounter();
+  unsigned long long t_loop0 = t_entry, t_loop1 = t_entry;
+#endif
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int n = lane & 31, g = lane >> 5;
@@ -534,6 +539,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
 #ifdef CP_PIPE_STAMPS
     unsigned long long st[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     unsigned long long t_prev = __builtin_readcyclecounter();
+    t_loop0 = t_prev;
 #endif
     for (int it = 0; it < n_live; ++it) {
       const bool has_next = it + 1 < n_live;
@@ -600,6 +606,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
 #ifdef CP_PIPE_STAMPS
     if (lane == 0 && split == 0 && kvh == 0 && blockIdx.x < 1024)
       for (int i = 0; i < 8; ++i) cp_dbg[(blockIdx.x * 8 + wave) * 8 + i] = i == 7 ? (unsigned long long)n_live : st[i];
+    t_loop1 = __builtin_readcyclecounter();
 #endif
     // back to buffer-0 addressing for the next chunk
     if (n_live & 1) {
@@ -665,4 +672,11 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
       if (r0 + rr < p.rows) *(floatx4_t*)(o + rl * D + c) = a;
     }
   }
+#ifdef CP_PIPE_STAMPS
+  if (lane == 0 && split == 0 && kvh == 0 && blockIdx.x < 1024) {
+    const unsigned long long t_end = __builtin_readcyclecounter();
+    unsigned long long* d2 = cp_dbg2 + (blockIdx.x * 8 + wave) * 4;
+    d2[0] = t_loop0 - t_entry; d2[1] = t_loop1 - t_loop0; d2[2] = t_end - t_loop1; d2[3] = t_entry;
+  }
+#endif
 }
