@@ -63,11 +63,7 @@ struct TileRegs {
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // K and V are read exactly once: streaming (non-temporal) loads
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
-#ifdef DEC_PLAIN_LOADS
-  return *(const uint4*)p;
-#else
   return __builtin_bit_cast(uint4, __builtin_nontemporal_load((const u32x4_t*)p));
-#endif
 }
 
 __device__ __forceinline__ void wave_lds_sync() {
@@ -326,10 +322,7 @@ int plan_splits(const cp_shape& s) {
   const int64_t wg_per_split = std::max<int64_t>(1, s.total_q * s.n_kv_heads);
   const int64_t avg_len = s.batch > 0 ? s.total_kv / s.batch : 0;
   int splits = 1;
-#ifndef CP_DEC_TARGET_WGS
-#define CP_DEC_TARGET_WGS 512
-#endif
-  while (splits < CP_MAX_PARTS && wg_per_split * splits * 2 <= CP_DEC_TARGET_WGS &&
+  while (splits < CP_MAX_PARTS && wg_per_split * splits * 2 <= 512 &&
          (int64_t)splits * 2 * 128 <= avg_len)
     splits *= 2;
   return splits;

@@ -171,6 +171,7 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
     return CP_ERR_WORKSPACE;
   if (pl.n_row_blocks == 0) return CP_OK;
   if (s.n_kv_heads > 65535 || pl.n_splits > 65535) return CP_ERR_SHAPE;
+  if (s.total_q * (s.n_q_heads / s.n_kv_heads) > 0x7fffffffLL) return CP_ERR_SHAPE;  // 31-bit rows
 
   char* ws = (char*)workspace;
   Params p;

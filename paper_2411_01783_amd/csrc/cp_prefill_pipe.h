@@ -98,6 +98,14 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
   return __builtin_bit_cast(unsigned, t);
 }
 
+// Workgroup barrier that orders LDS traffic only: global loads issued before it (the Q
+// fragments, the tile-bound prefetch) stay in flight across it.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Everything a wavefront carries from block to block. All indices are compile-time.
 struct PipeRegs {
   floatx16_t o[4];         // O^T accumulators, 4 blocks of 32 channels
@@ -110,7 +118,7 @@ struct PipeRegs {
 
 #ifdef CP_PIPE_STAMPS
 __device__ unsigned long long cp_dbg[1024 * 8 * 8];
-__device__ unsigned long long cp_dbg2[1024 * 8 * 4];
+__device__ unsigned long long cp_dbg2[1024 * 8 * 8];
 #define CP_STAMP(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st[i] += t_ - t_prev; t_prev = t_; } while (0)
 #else
 #define CP_STAMP(i) do { } while (0)
@@ -145,8 +153,6 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
   constexpr int kBound[15] = {0, 1, 2, 3, 5, 6, 7, 8, 9, 10, 11, 13, 14, 15, 16};
 
   floatx16_t& s = R.s[CUR];
-  float dm[4] = {R.l_run, R.l_run + 1.f, R.l_run + 2.f, R.l_run + 3.f}; (void)dm;
-  unsigned dacc = 0; (void)dacc;
   float e[16];
   float m_use = 0.f, alpha = 1.f;
   float lsum0 = 0.f, lsum1 = 0.f;
@@ -179,11 +185,7 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
       unsigned pk = pack_bf16(e[v - 1], e[v]);
       pin(pk);
       pin(lsum1);
-#ifdef CP_X_DUMMYOUT
-      dacc ^= pk;
-#else
       R.pb[CUR][v >> 3][(v & 7) >> 1] = pk;
-#endif
     } else {
       lsum0 += e[v];
       pin(lsum0);
@@ -224,19 +226,10 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
       }
       pin(m_use);
     } else {
-#ifdef CP_X_NOVALU
-      if (true) return;
-#endif
       if constexpr (J <= 14) {
 #pragma unroll
         for (int v = kBound[J - 1]; v < kBound[J]; ++v) {
-#if defined(CP_X_DUMMYIN)
-          e[v] = __builtin_amdgcn_exp2f(fmaf(dm[v & 3], scale_log2, -m_use));
-#elif defined(CP_X_NOEXP)
-          e[v] = fmaf(s[v], scale_log2, -m_use) * 1e-30f;
-#else
           e[v] = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -m_use));
-#endif
           pin(e[v]);
         }
       }
@@ -255,9 +248,7 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
     lgkm_wait<14 - 2 * M + M>(R.vf[M]);
     R.o[M & 3] = mfma32(__builtin_bit_cast(bf16x8_t, R.vf[M]),
                         __builtin_bit_cast(bf16x8_t, R.pb[NXT][M >> 2]), R.o[M & 3]);
-#ifndef CP_X_NOLDS
     R.kf[M] = lds_read_b128<KOFF>(kaddr[M]);
-#endif
     hook(IntC<M>{});
     valu(IntC<M>{});
     __builtin_amdgcn_sched_barrier(0);
@@ -278,9 +269,7 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
     } else {
       R.s[NXT] = mfma32(__builtin_bit_cast(bf16x8_t, R.kf[M]), qf[M], R.s[NXT]);
     }
-#ifndef CP_X_NOLDS
     R.vf[M] = lds_read_vt_frag<VOFF + (M >> 2) * 16 * ROW_BYTES>(vaddr[M & 3]);
-#endif
     hook(IntC<8 + M>{});
     valu(IntC<8 + M>{});
     __builtin_amdgcn_sched_barrier(0);
@@ -309,9 +298,6 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
     blk = lsum0 + lsum1;
   }
   R.l_run += blk;
-#ifdef CP_X_DUMMYOUT
-  R.l_run += (float)(dacc & 1);
-#endif
   // rows whose reference maximum moved: bring O to the new reference (rare)
   if (__builtin_expect(__builtin_amdgcn_ballot_w64(raise) != 0, 0)) {
 #pragma unroll
@@ -337,7 +323,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
 
 #ifdef CP_PIPE_STAMPS
   const unsigned long long t_entry = __builtin_readcyclecounter();
-  unsigned long long t_loop0 = t_entry, t_loop1 = t_entry;
+  unsigned long long t_loop0 = t_entry, t_loop1 = t_entry, t_p1 = t_entry, t_p2 = t_entry, t_p3 = t_entry;
 #endif
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -347,15 +333,23 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   const int split = blockIdx.z;
 
   // ---- this lane's query row ----
+  // (rows fit 31 bits: checked by the launcher)
   const int64_t r = (int64_t)row_block * BM + wave * 32 + n;
   const bool row_ok = r < p.rows;
-  const int64_t token = row_ok ? r / p.group : 0;
+  const int64_t token = row_ok ? (int64_t)((uint32_t)r / (uint32_t)p.group) : 0;
   const int hg = row_ok ? (int)(r - token * p.group) : 0;
   const int64_t row_lin = (token * p.n_kv_heads + kvh) * p.group + hg;  // index into [tokens, N_H]
   const int32_t qp = row_ok ? p.q_pos[token] : CP_POS_PAD_Q;
   const int32_t ql = BAND && row_ok ? p.q_lo[token] : INT32_MIN;
   const int32_t total_kv = p.total_kv;
   const float scale_log2 = p.scale_log2;
+  // The start-up chain is q_pos -> visible tiles -> first tile; the bounds of the first 512
+  // tiles are requested now so that they arrive together with q_pos, and the Q fragments
+  // (needed last) are requested after both and waited for only before the first product.
+  const int t_begin = split * p.tiles_per_split;
+  const int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
+  int2 first_bounds = make_int2(0, 0);
+  if (t_begin + wave * 64 + lane < t_end) first_bounds = tile_bounds[t_begin + wave * 64 + lane];
 
   bf16x8_t qf[8];
 #pragma unroll
@@ -383,7 +377,10 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     wg_scratch[wave] = w_qmax;
     if (BAND) wg_scratch[NWAVE + 1 + wave] = w_lomin;
   }
-  __syncthreads();
+  lds_barrier();
+#ifdef CP_PIPE_STAMPS
+  t_p1 = __builtin_readcyclecounter();
+#endif
   int wg_qmax = INT32_MIN, wg_lomin = INT32_MAX;
 #pragma unroll
   for (int w = 0; w < NWAVE; ++w) {
@@ -411,7 +408,6 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   // rows (1 KiB) per instruction and tile; lane l covers row l/16 of the four, chunk position
   // l%16. Part I of a tile is one such instruction for K and one for V. `rows_valid` clamps
   // rows past the end of the shard to its last row (they are masked by their position).
-  int first_key0 = 0; (void)first_key0;
   const uint32_t stride_b = (uint32_t)p.n_kv_heads * ROW_BYTES;  // bytes between tokens
   const int l_row = lane >> 4, l_pos = lane & 15;
   const uint32_t v_chunk = (l_pos ^ ((l_row & 3) * 4)) * 16;
@@ -419,9 +415,6 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   const char* const v_head = (const char*)p.v + (int64_t)kvh * ROW_BYTES;
   auto issue_part = [&](auto ic, int key0, int b) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value;
-#ifdef CP_X_NODMA
-    if (b >= 0 && key0 != first_key0) return;
-#endif
     const int row = wave * 16 + I * 4 + l_row;
     const uint32_t row_c = (uint32_t)min(row, total_kv - 1 - key0);
     const uint32_t roff = __umul24(row_c, stride_b);
@@ -459,23 +452,21 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
                 (vq >> 1) * 16 + (vq & 1) * 8 + (db ^ vj) * 64;
   uint32_t paddr = smem_lds + OFF_POS8 + g * 16;
 
-  const int t_begin = split * p.tiles_per_split;
-  const int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
   for (int c0 = t_begin; c0 < t_end; c0 += MAX_LIVE) {
     // Compact the tiles some query of the workgroup can see (smallest key position not
     // beyond the largest query position) into an ascending list in LDS: (tile, min, max).
-    __syncthreads();  // previous chunk (list, tile buffers) fully consumed
+    lds_barrier();  // previous chunk (list, tile buffers) fully consumed
     {
       const int t = c0 + wave * 64 + lane;
       int2 b = make_int2(0, 0);
       bool lv = false;
       if (t < t_end) {
-        b = tile_bounds[t];
+        b = c0 == t_begin ? first_bounds : tile_bounds[t];
         lv = b.x <= wg_qmax && (!BAND || b.y >= wg_lomin);
       }
       const uint64_t mask = __builtin_amdgcn_ballot_w64(lv);
       if (lane == 0) wg_scratch[wave] = __builtin_popcountll(mask);
-      __syncthreads();
+      lds_barrier();
       int base = 0, total = 0;
 #pragma unroll
       for (int w = 0; w < NWAVE; ++w) {
@@ -488,16 +479,16 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
             make_int4(t, b.x, b.y, 0);
       if (tid == 0) wg_scratch[NWAVE] = total;
     }
-    __syncthreads();
+    lds_barrier();
     const int n_live = __builtin_amdgcn_readfirstlane(wg_scratch[NWAVE]);
     if (n_live == 0) continue;
+#ifdef CP_PIPE_STAMPS
+    t_p2 = __builtin_readcyclecounter();
+#endif
 
     // ---- prologue: tile 0 into buffer 0, Q stage of block 0 ----
     int32_t next_pos = 0;
     bool need_mask, next_mask = false;
-#ifdef CP_X_NODMA
-    first_key0 = __builtin_amdgcn_readfirstlane(live[0].x) * TILE;
-#endif
     int next_key0 = 0;
     auto read_entry = [&](int idx, int& key0, bool& mask_it) {
       const int4 e = live[idx < n_live ? idx : n_live - 1];
@@ -517,6 +508,9 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
       const int32_t pos = load_pos(key0);
       if (tid < TILE) posbuf0[tid] = pos;
       __syncthreads();  // waits for the tile (vmcnt) and publishes it
+#ifdef CP_PIPE_STAMPS
+      t_p3 = __builtin_readcyclecounter();
+#endif
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) R.kf[ks] = lds_read_b128<0>(kaddr[ks]);
       lgkm_wait<0>(R.kf[0], R.kf[1], R.kf[2], R.kf[3]);
@@ -572,9 +566,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
       const bool cur_mask = need_mask;
       need_mask = next_mask;
       read_entry(it + 2, next_key0, next_mask);  // no direct-to-LDS load is in flight here
-#ifndef CP_X_NOBAR
       __syncthreads();
-#endif
       CP_STAMP(2);
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) kaddr[ks] ^= KD_BYTES;  // K of the next tile from here on
@@ -582,9 +574,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
       // barrier X: every LDS read of this tile has completed; its buffers may be refilled
       __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
       CP_STAMP(3);
-#ifndef CP_X_NOBAR
       __syncthreads();
-#endif
       CP_STAMP(4);
 #pragma unroll
       for (int db = 0; db < 4; ++db) vaddr[db] ^= KD_BYTES;
@@ -675,8 +665,9 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
 #ifdef CP_PIPE_STAMPS
   if (lane == 0 && split == 0 && kvh == 0 && blockIdx.x < 1024) {
     const unsigned long long t_end = __builtin_readcyclecounter();
-    unsigned long long* d2 = cp_dbg2 + (blockIdx.x * 8 + wave) * 4;
+    unsigned long long* d2 = cp_dbg2 + (blockIdx.x * 8 + wave) * 8;
     d2[0] = t_loop0 - t_entry; d2[1] = t_loop1 - t_loop0; d2[2] = t_end - t_loop1; d2[3] = t_entry;
+    d2[4] = t_p1 - t_entry; d2[5] = t_p2 - t_p1; d2[6] = t_p3 - t_p2; d2[7] = t_loop0 - t_p3;
   }
 #endif
 }
