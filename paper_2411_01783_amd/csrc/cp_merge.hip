@@ -59,13 +59,9 @@ __device__ __forceinline__ void store_vec<bf16_t, 8>(bf16_t* p, const float (&x)
 }
 
 // NP > 0: compile-time part count (fully unrolled); NP == 0: run-time count.
-// STRIDED: partials are parts_out + s * stride (split-KV scratch) instead of pointers.
-template <typename TP, typename TO, int VEC, int NP, bool STRIDED>
-__global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float* parts_out,
-                                                     const float* parts_lse,
-                                                     int64_t part_stride_rows, int n_parts_rt,
-                                                     int64_t rows, int head_dim,
-                                                     TO* __restrict__ out,
+template <typename TP, typename TO, int VEC, int NP>
+__global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, int n_parts_rt, int64_t rows,
+                                                     int head_dim, TO* __restrict__ out,
                                                      float* __restrict__ lse_out) {
   const int n_parts = NP > 0 ? NP : n_parts_rt;
   const int vec_per_row = head_dim / VEC;
@@ -81,7 +77,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float*
     float lv[NP > 0 ? NP : 1];
 #pragma unroll
     for (int s = 0; s < n_parts; ++s) {
-      const float x = STRIDED ? parts_lse[s * part_stride_rows + row] : ptrs.lse[s][row];
+      const float x = ptrs.lse[s][row];
       if (NP > 0) lv[NP > 0 ? s : 0] = x;
       lmax = fmaxf(lmax, x);
     }
@@ -89,40 +85,15 @@ __global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float*
 #pragma unroll
     for (int i = 0; i < VEC; ++i) acc[i] = 0.f;
     float den = 0.f;
-    if constexpr (STRIDED && NP > 0 && NP <= 16) {
-      // Split-KV scratch of one call: few rows, so the kernel is bound by latency, not by
-      // bandwidth. Every row of the scratch is written (finite zeros when empty), so all NP
-      // loads are issued at once, next to the LSE loads, and the arithmetic is branch-free
-      // (a branch on the weights would pull the loads behind the wait for the LSE values).
-      float xs[NP][VEC];
-#pragma unroll
-      for (int s = 0; s < NP; ++s)
-        load_vec<TP, VEC>((const TP*)(parts_out + (s * part_stride_rows + row) * head_dim) + col,
-                          xs[s]);
-      __builtin_amdgcn_sched_barrier(0);  // keep the NP loads together, ahead of the arithmetic
-      const bool any = lmax != -INFINITY;
-#pragma unroll
-      for (int s = 0; s < NP; ++s) {
-        const float w = any ? __expf(lv[s] - lmax) : 0.f;  // exp(-inf) = 0 for empty partials
-        den += w;
-#pragma unroll
-        for (int i = 0; i < VEC; ++i) acc[i] = fmaf(w, xs[s][i], acc[i]);
-      }
-      const float inv = any ? 1.f / den : 0.f;
-#pragma unroll
-      for (int i = 0; i < VEC; ++i) acc[i] *= inv;
-    } else if (lmax != -INFINITY) {
+    if (lmax != -INFINITY) {
 #pragma unroll
       for (int s = 0; s < n_parts; ++s) {
-        const float x = NP > 0 ? lv[NP > 0 ? s : 0]
-                               : (STRIDED ? parts_lse[s * part_stride_rows + row] : ptrs.lse[s][row]);
+        const float x = NP > 0 ? lv[NP > 0 ? s : 0] : ptrs.lse[s][row];
         const float w = __expf(x - lmax);  // exp(-inf) = 0 for empty partials
         den += w;
-        // split-KV scratch rows are always written (zeros when empty), so their loads need
-        // not wait for the weights; caller-supplied partials with zero weight are not read
-        if (STRIDED || w != 0.f) {
-          const TP* p = STRIDED ? (const TP*)(parts_out + (s * part_stride_rows + row) * head_dim)
-                                : (const TP*)ptrs.out[s] + row * head_dim;
+        // a partial with zero weight is not read (its O may hold anything)
+        if (w != 0.f) {
+          const TP* p = (const TP*)ptrs.out[s] + row * head_dim;
           float x4[VEC];
           load_vec<TP, VEC>(p + col, x4);
 #pragma unroll
@@ -139,32 +110,77 @@ __global__ __launch_bounds__(256) void merge_kernel(MergePtrs ptrs, const float*
   }
 }
 
-template <typename TP, typename TO, int VEC, bool STRIDED>
-int launch_np(const MergePtrs& ptrs, const float* parts_out, const float* parts_lse,
-              int64_t stride, int n_parts, int64_t rows, int head_dim, void* out, float* lse_out,
-              hipStream_t stream) {
+// Split-KV scratch of one call (partials s * stride apart, every row written: finite zeros
+// and LSE = -inf when a split saw nothing). Few rows, so the kernel is bound by latency, not
+// by bandwidth: a thread requests the LSE values of all parts and 16 data vectors at a time
+// back to back, and the arithmetic is branch-free (a branch on the weights would pull the
+// loads behind the wait for the LSE values).
+template <typename TO>
+__global__ __launch_bounds__(64) void merge_split_kernel(const float* __restrict__ parts_out,
+                                                         const float* __restrict__ parts_lse,
+                                                         int64_t part_stride_rows, int n_parts,
+                                                         int64_t rows, int head_dim,
+                                                         TO* __restrict__ out,
+                                                         float* __restrict__ lse_out) {
+  constexpr int VEC = 4, BATCH = 16;
+  const int vec_per_row = head_dim / VEC;
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= rows * vec_per_row) return;
+  const int64_t row = idx / vec_per_row;
+  const int col = (int)(idx - row * vec_per_row) * VEC;
+  float lv[CP_MAX_PARTS];
+#pragma unroll
+  for (int s = 0; s < CP_MAX_PARTS; ++s)
+    lv[s] = s < n_parts ? parts_lse[s * part_stride_rows + row] : -INFINITY;
+  float acc[VEC] = {0.f, 0.f, 0.f, 0.f};
+  float den = 0.f, lmax = -INFINITY;
+#pragma unroll
+  for (int b = 0; b < CP_MAX_PARTS / BATCH; ++b) {
+    if (b * BATCH >= n_parts) break;  // uniform
+    float xs[BATCH][VEC];
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) {
+      const int s = min(b * BATCH + i, n_parts - 1);  // parts past the end: weight 0 below
+      load_vec<float, VEC>(parts_out + (s * part_stride_rows + row) * head_dim + col, xs[i]);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // keep the requests together, ahead of the arithmetic
+    if (b == 0) {
+#pragma unroll
+      for (int s = 0; s < CP_MAX_PARTS; ++s) lmax = fmaxf(lmax, lv[s]);
+    }
+    const bool any = lmax != -INFINITY;
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) {
+      const float w = any ? __expf(lv[b * BATCH + i] - lmax) : 0.f;  // exp(-inf) = 0
+      den += w;
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) acc[c] = fmaf(w, xs[i][c], acc[c]);
+    }
+  }
+  const float inv = den > 0.f ? 1.f / den : 0.f;
+#pragma unroll
+  for (int c = 0; c < VEC; ++c) acc[c] *= inv;
+  store_vec<TO, VEC>(out + row * head_dim + col, acc);
+  if (lse_out != nullptr && col == 0)
+    lse_out[row] = den > 0.f ? lmax + __logf(den) : -INFINITY;
+}
+
+template <typename TP, typename TO, int VEC>
+int launch_np(const MergePtrs& ptrs, int n_parts, int64_t rows, int head_dim, void* out,
+              float* lse_out, hipStream_t stream) {
   const int64_t n_vec = rows * (head_dim / VEC);
   if (n_vec == 0) return CP_OK;
-  // Small merges (the split partials of a decode step) are latency-bound: one wavefront per
-  // workgroup spreads them over every CU instead of a quarter of them.
-#ifndef CP_MERGE_SMALL_VEC
-#define CP_MERGE_SMALL_VEC (256 * 256)
-#endif
-  const int threads = n_vec <= CP_MERGE_SMALL_VEC ? 64 : 256;
-  int64_t blocks = (n_vec + threads - 1) / threads;
+  int64_t blocks = (n_vec + 255) / 256;
   const int64_t cap = 256 * 32;  // grid-stride beyond 32 workgroups per CU
   if (blocks > cap) blocks = cap;
-#define CP_MERGE_LAUNCH(NP)                                                                   \
-  hipLaunchKernelGGL((merge_kernel<TP, TO, VEC, NP, STRIDED>), dim3((unsigned)blocks),        \
-                     dim3(threads), 0, stream, ptrs, parts_out, parts_lse, stride, n_parts,   \
-                     rows, head_dim, (TO*)out, lse_out)
+#define CP_MERGE_LAUNCH(NP)                                                                  \
+  hipLaunchKernelGGL((merge_kernel<TP, TO, VEC, NP>), dim3((unsigned)blocks), dim3(256), 0,  \
+                     stream, ptrs, n_parts, rows, head_dim, (TO*)out, lse_out)
   switch (n_parts) {
     case 2: CP_MERGE_LAUNCH(2); break;
     case 4: CP_MERGE_LAUNCH(4); break;
     case 8: CP_MERGE_LAUNCH(8); break;
     case 16: CP_MERGE_LAUNCH(16); break;
-    case 32: if (STRIDED) { CP_MERGE_LAUNCH(32); } else { CP_MERGE_LAUNCH(0); } break;
-    case 64: if (STRIDED) { CP_MERGE_LAUNCH(64); } else { CP_MERGE_LAUNCH(0); } break;
     default: CP_MERGE_LAUNCH(0); break;
   }
 #undef CP_MERGE_LAUNCH
@@ -183,27 +199,28 @@ int launch_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* co
   }
   if (part_dtype == CP_FP32) {
     if (out_dtype == CP_FP32)
-      return launch_np<float, float, 4, false>(ptrs, nullptr, nullptr, 0, n_parts, rows,
-                                               head_dim, out, lse_out, stream);
-    return launch_np<float, bf16_t, 4, false>(ptrs, nullptr, nullptr, 0, n_parts, rows, head_dim,
-                                              out, lse_out, stream);
+      return launch_np<float, float, 4>(ptrs, n_parts, rows, head_dim, out, lse_out, stream);
+    return launch_np<float, bf16_t, 4>(ptrs, n_parts, rows, head_dim, out, lse_out, stream);
   }
   if (out_dtype == CP_FP32)
-    return launch_np<bf16_t, float, 8, false>(ptrs, nullptr, nullptr, 0, n_parts, rows, head_dim,
-                                              out, lse_out, stream);
-  return launch_np<bf16_t, bf16_t, 8, false>(ptrs, nullptr, nullptr, 0, n_parts, rows, head_dim,
-                                             out, lse_out, stream);
+    return launch_np<bf16_t, float, 8>(ptrs, n_parts, rows, head_dim, out, lse_out, stream);
+  return launch_np<bf16_t, bf16_t, 8>(ptrs, n_parts, rows, head_dim, out, lse_out, stream);
 }
 
 int launch_merge_strided(int64_t rows, int32_t head_dim, int32_t n_parts, const float* parts_out,
                          const float* parts_lse, int64_t part_stride_rows, void* out,
                          int32_t out_dtype, float* lse_out, hipStream_t stream) {
-  MergePtrs ptrs = {};
+  const int64_t n_vec = rows * (head_dim / 4);
+  if (n_vec == 0) return CP_OK;
+  if (n_parts < 1 || n_parts > CP_MAX_PARTS || n_vec > 0x7fffffffLL * 64) return CP_ERR_SHAPE;
+  const dim3 grid((unsigned)((n_vec + 63) / 64));
   if (out_dtype == CP_FP32)
-    return launch_np<float, float, 4, true>(ptrs, parts_out, parts_lse, part_stride_rows,
-                                            n_parts, rows, head_dim, out, lse_out, stream);
-  return launch_np<float, bf16_t, 4, true>(ptrs, parts_out, parts_lse, part_stride_rows, n_parts,
-                                           rows, head_dim, out, lse_out, stream);
+    hipLaunchKernelGGL(merge_split_kernel<float>, grid, dim3(64), 0, stream, parts_out, parts_lse,
+                       part_stride_rows, n_parts, rows, head_dim, (float*)out, lse_out);
+  else
+    hipLaunchKernelGGL(merge_split_kernel<bf16_t>, grid, dim3(64), 0, stream, parts_out,
+                       parts_lse, part_stride_rows, n_parts, rows, head_dim, (bf16_t*)out, lse_out);
+  return check_launch();
 }
 
 }  // namespace cp

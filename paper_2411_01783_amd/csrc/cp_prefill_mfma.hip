@@ -196,10 +196,14 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
 
   const dim3 grid(pl.n_row_blocks, s.n_kv_heads, pl.n_splits);
   const bool direct_bf16 = pl.n_splits == 1 && out_dtype == CP_BF16;
-  auto kern = q_lo != nullptr ? (direct_bf16 ? prefill_mfma_kernel<bf16_t, true>
-                                             : prefill_mfma_kernel<float, true>)
-                              : (direct_bf16 ? prefill_mfma_kernel<bf16_t, false>
-                                             : prefill_mfma_kernel<float, false>);
+  const bool band = q_lo != nullptr;
+  auto kern = pl.n_splits > 1
+                  ? (band ? prefill_mfma_kernel<float, true, true> : prefill_mfma_kernel<float, false, true>)
+                  : direct_bf16
+                        ? (band ? prefill_mfma_kernel<bf16_t, true, false>
+                                : prefill_mfma_kernel<bf16_t, false, false>)
+                        : (band ? prefill_mfma_kernel<float, true, false>
+                                : prefill_mfma_kernel<float, false, false>);
   constexpr int kSmem = SMEM_BYTES8;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                           kSmem) != hipSuccess)

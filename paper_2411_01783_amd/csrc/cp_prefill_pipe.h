@@ -310,7 +310,8 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
 
 // BAND: packed batch. Positions are shifted per sequence and a query also has a lower bound
 // q_lo (the shift of its sequence): visible iff q_lo <= kv_pos <= q_pos.
-template <typename TO, bool BAND>
+// SPLIT: the launch splits the KV axis over grid.z and writes fp32 partials to the workspace.
+template <typename TO, bool BAND, bool SPLIT>
 __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     Params p, const int2* __restrict__ tile_bounds) {
   extern __shared__ __align__(16) char smem[];
@@ -613,7 +614,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   const float lse_val =
       l_tot > 0.f ? (R.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
-  const bool direct = p.n_splits == 1;
+  constexpr bool direct = !SPLIT;
   float* const lse_dst = direct ? p.lse : p.part_lse + (int64_t)split * p.rows_all_heads;
   if (row_ok && g == 0) lse_dst[row_lin] = lse_val;
 
