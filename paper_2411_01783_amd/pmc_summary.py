@@ -14,8 +14,9 @@ import csv
 import os
 import sys
 
-KERNELS = {"prefill_mfma_kernel": "prefill_mfma_kernel", "decode_kernel": "decode_kernel",
-           "merge_kernel": "merge_kernel"}
+# kernel-name substring -> tag of the summary file (first match wins)
+KERNELS = [("prefill_mfma_kernel", "prefill_mfma_kernel"), ("decode_kernel", "decode_kernel"),
+           ("merge_split_kernel", "merge_kernel_split"), ("merge_kernel", "merge_kernel_ring")]
 COPY_MARK = "MulFunctor"
 
 
@@ -30,11 +31,10 @@ def per_dispatch(path: str, counter: str):
         if COPY_MARK in name:
             tag = "copy"
         else:
-            for k in KERNELS:
+            for k, t in KERNELS:
                 if k in name:
-                    tag = k
-                    if k == "merge_kernel":
-                        tag += "_split" if "true" in name or "Lb1" in name else "_ring"
+                    tag = t
+                    break
         if tag is not None:
             acc[tag][r["Dispatch_Id"]] += float(r["Counter_Value"])
     return {k: list(v.values()) for k, v in acc.items()}

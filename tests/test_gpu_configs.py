@@ -40,9 +40,7 @@ def test_prefill_128k_passkv_ring_sampled(oracle):
     q, k, v = W.qkv(w, device="cuda")
     pos, qs, ks, vs = _shard(w, q, k, v)
     ps = [i32(p) for p in pos]
-    # as bench.py runs it: a rank's calls alternate between two streams
-    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32,
-                  aux_stream=torch.cuda.Stream())
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
     out, lse = B.cp_ring_passkv(ring)
     torch.cuda.synchronize()
     k64, v64 = W.to_f64(k), W.to_f64(v)
