@@ -387,6 +387,15 @@ def main():
                                             PEAK_HBM_GBS, 4)}},
     }
     result["aux"]["per_call"] = per_call_prefill(w, st)
+    if not args.no_aux and w.name == "prefill_128k":
+        # the same ring with bf16 partial outputs (the width the paper's All2All model assumes);
+        # the headline keeps fp32 partials
+        ring16 = B.Ring(st["qs"], st["ks"], st["vs"], st["ps"], st["ps"], out_dtype=torch.bfloat16,
+                        part_dtype=torch.bfloat16)
+        sec16 = time_steps(lambda: B.cp_ring_passkv(ring16), args.steps, args.warmup)
+        result["aux"]["ring_bf16_partials"] = {"tflops": round(flop_step / sec16 / 1e12, 2),
+                                               "ms_per_rank": round(sec16 * 1e3 / w.n_ranks, 3)}
+        del ring16
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline_prefill(w, st)
     del st, ring

@@ -247,6 +247,25 @@ def test_mfma_load_balanced_partials_and_merge(oracle, n, t, two_streams):
         check(out_q[a], lse_q[a], ref_o[pos[a]], ref_l[pos[a]], what="pass-Q rank %d" % a)
 
 
+def test_ring_passkv_bf16_partials(oracle):
+    # partial outputs stored as bf16 (LSE stays fp32): merged result within the same bar
+    n, t = 4, 2048
+    q, q64 = randn(45, (t, 16, 128))
+    k, k64 = randn(46, (t, 1, 128))
+    v, v64 = randn(47, (t, 1, 128))
+    pos = [B.cp_shard_positions(t, n, r) for r in range(n)]
+    ref_o, ref_l = oracle.unsharded_causal(q64, k64, v64)
+    ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                  [i32(p) for p in pos], [i32(p) for p in pos], keep_partials=True,
+                  out_dtype=torch.bfloat16, part_dtype=torch.bfloat16)
+    out, lse = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    for a in range(n):
+        check(out[a], lse[a], ref_o[pos[a]], ref_l[pos[a]], what="merged rank %d" % a)
+    po, pl = oracle.attn(q64[pos[3]], k64[pos[1]], v64[pos[1]], pos[3], pos[1])
+    check(*ring.partial(3, 1), po, pl, what="bf16 partial 3,1")
+
+
 def test_mfma_split_kv_short_query_shard(oracle):
     # 40 query tokens x 16 heads (3 row blocks) against 3000 keys: the KV axis is split
     tq, tkv = 40, 3000
