@@ -129,6 +129,30 @@ int cp_attn_partial(const cp_shape* shape, const void* q, const void* k, const v
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Partial attention merged into a running result: (acc_out, acc_lse) <- merge((acc_out,
+ * acc_lse), Attn(Q, KV)) with the merge of Appendix B, Equation 4 (and the LSE of the union
+ * of the key sets), which may be applied step by step because it is associative. One launch:
+ * the merge happens in the attention kernel's epilogue, so a ring of N steps needs neither N
+ * partial buffers nor a merge pass.
+ *
+ *   acc_out    (device) fp32 [total_q, n_q_heads, head_dim], read and written
+ *   acc_lse    (device) fp32 [total_q, n_q_heads], read and written. The first step of a
+ *              ring is a plain cp_attn_partial into (acc_out, acc_lse) with out_dtype CP_FP32.
+ *   final_out  (device) or NULL. Not NULL (last step): the merged O is written there in
+ *              final_dtype and acc_out is left as it was; acc_lse is still updated.
+ *   final_lse  (device) fp32 or NULL: a copy of the merged LSE.
+ *   other arguments as cp_attn_partial.
+ * Rows of which this step sees no key are not touched (with final_out: copied from acc_out).
+ * Errors: as cp_attn_partial; CP_ERR_UNSUPPORTED unless the call runs on the MFMA kernel
+ * without a KV split (bf16, head_dim 128, batch 1, at least 128 row blocks of 256 rows).
+ */
+int cp_attn_partial_accumulate(const cp_shape* shape, const void* q, const void* k,
+                               const void* v, const int32_t* q_pos, const int32_t* kv_pos,
+                               float* acc_out, float* acc_lse, void* final_out,
+                               int32_t final_dtype, float* final_lse, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+/*
  * Decode attention of one pass-Q ring step: Algorithm 4,
  * "O_s^k <- GQA(Q^s_k, KV_k[bid^s_k])". Each of the shape->total_q query tokens
  * (one per travelling sequence) attends to the KV segment of its own sequence
@@ -202,7 +226,14 @@ typedef struct {
   void* partial_out;
   float* partial_lse;
   int32_t keep_partials;
-  int32_t reserved;
+  /*
+   * 1: prefill drivers merge in the epilogues instead of keeping N partials per rank
+   * (cp_attn_partial_accumulate): step 0 of a rank writes a running (O, LSE) into partial
+   * slot 0, the following steps merge into it and the last one writes the rank's output.
+   * One slot suffices; no merge pass. Requires part_dtype == CP_FP32, keep_partials == 0, no
+   * decode, and calls that do not split their KV axis (else CP_ERR_UNSUPPORTED). 0: off.
+   */
+  int32_t fused_merge;
   void* workspace; /* (device) max over ranks of the per-call workspace */
   size_t workspace_bytes;
   /* decode only (cp_ring_passq_decode); NULL otherwise */

@@ -23,7 +23,8 @@ CP_POS_PAD_Q = -1
 CP_MAX_PARTS = 64
 
 EXPORTS = [
-    "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_decode",
+    "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_partial_accumulate",
+    "cp_attn_decode",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
     "cp_ring_workspace_bytes", "cp_select_order", "cp_probe_mfma_rate", "cp_strerror",
     "cp_version",
@@ -49,7 +50,7 @@ class cp_ring_desc(ctypes.Structure):
                 ("q_pos", ctypes.POINTER(_vp)), ("kv_pos", ctypes.POINTER(_vp)),
                 ("out", ctypes.POINTER(_vp)), ("lse", ctypes.POINTER(_vp)),
                 ("partial_out", _vp), ("partial_lse", _vp),
-                ("keep_partials", _i32), ("reserved", _i32),
+                ("keep_partials", _i32), ("fused_merge", _i32),
                 ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t),
                 ("batch", _i32),
                 ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp)),
@@ -112,6 +113,9 @@ def load() -> ctypes.CDLL:
     lib.cp_select_order.restype = ctypes.c_int
     lib.cp_select_order.argtypes = [ctypes.POINTER(cp_select_params), _i64, _i64, _i32,
                                     ctypes.POINTER(_i32)]
+    lib.cp_attn_partial_accumulate.restype = ctypes.c_int
+    lib.cp_attn_partial_accumulate.argtypes = [ctypes.POINTER(cp_shape)] + [_vp] * 8 + [_i32] + \
+        [_vp] * 2 + [ctypes.c_size_t, _vp]
     lib.cp_probe_mfma_rate.restype = ctypes.c_int
     lib.cp_probe_mfma_rate.argtypes = [_vp, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
     _lib = lib
@@ -242,6 +246,26 @@ def cp_attn_partial(q, k, v, q_pos, kv_pos, cu_seqlens_q=None, cu_seqlens_kv=Non
     return out, lse
 
 
+def cp_attn_partial_accumulate(q, k, v, q_pos, kv_pos, acc_out, acc_lse, final_out=None,
+                               final_lse=None, softmax_scale: float = 0.0, workspace=None,
+                               stream=None):
+    """Merge Attn(q, kv) into the running fp32 (acc_out, acc_lse); see the header."""
+    lib = load()
+    tq, nh, d = q.shape
+    tkv, nkv, _ = k.shape
+    shape = make_shape(dtype_code(q.dtype), d, nh, nkv, tq, tkv, 1, softmax_scale)
+    assert acc_out.dtype == torch.float32 and acc_lse.dtype == torch.float32
+    if workspace is None:
+        workspace = _workspace(cp_workspace_bytes(shape, CP_WS_PARTIAL), q.device)
+    wp, wn = _ws_ptr(workspace)
+    fdt = dtype_code(final_out.dtype) if final_out is not None else CP_FP32
+    _check(lib.cp_attn_partial_accumulate(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v),
+                                          _ptr(q_pos), _ptr(kv_pos), _ptr(acc_out), _ptr(acc_lse),
+                                          _ptr(final_out), fdt, _ptr(final_lse), wp, wn,
+                                          _stream(stream)), "cp_attn_partial_accumulate")
+    return (final_out if final_out is not None else acc_out), acc_lse
+
+
 def cp_attn_decode(q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid,
                    out_dtype: Optional[torch.dtype] = None, softmax_scale: float = 0.0,
                    out=None, lse=None, workspace=None, stream=None):
@@ -295,7 +319,8 @@ class Ring:
                  out_dtype: Optional[torch.dtype] = None, part_dtype: torch.dtype = torch.float32,
                  keep_partials: bool = False, softmax_scale: float = 0.0,
                  cu_seqlens_kv: Optional[List[torch.Tensor]] = None,
-                 bid: Optional[List[torch.Tensor]] = None, aux_stream=None):
+                 bid: Optional[List[torch.Tensor]] = None, aux_stream=None,
+                 fused_merge: bool = False):
         n = len(q)
         self.n = n
         self.decode = cu_seqlens_kv is not None
@@ -309,7 +334,7 @@ class Ring:
         self.out = [torch.empty((m, nh, d), dtype=odt, device=dev) for m in self.n_q]
         self.lse = [torch.empty((m, nh), dtype=torch.float32, device=dev) for m in self.n_q]
         max_q = max(self.n_q) if self.n_q else 0
-        slots = n * n if keep_partials else n
+        slots = n * n if keep_partials else (1 if fused_merge else n)
         self.keep = keep_partials
         self.partial_out = torch.empty((slots, max_q, nh, d), dtype=part_dtype, device=dev)
         self.partial_lse = torch.empty((slots, max_q, nh), dtype=torch.float32, device=dev)
@@ -329,6 +354,7 @@ class Ring:
             setattr(dsc, name, ctypes.cast(arr, type(getattr(dsc, name))))
         dsc.partial_out, dsc.partial_lse = _ptr(self.partial_out), _ptr(self.partial_lse)
         dsc.keep_partials = 1 if keep_partials else 0
+        dsc.fused_merge = 1 if fused_merge else 0
         if self.decode:
             self._cu = (_vp * n)(*[_ptr(t) for t in cu_seqlens_kv])
             self._bid = (_vp * n)(*[(_ptr(t) if t.numel() > 0 else None) for t in bid])

@@ -135,6 +135,34 @@ int cp_attn_partial(const cp_shape* shape, const void* q, const void* k, const v
                                 out, lse, out_dtype, st);
 }
 
+int cp_attn_partial_accumulate(const cp_shape* shape, const void* q, const void* k,
+                               const void* v, const int32_t* q_pos, const int32_t* kv_pos,
+                               float* acc_out, float* acc_lse, void* final_out,
+                               int32_t final_dtype, float* final_lse, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != CP_OK) return rc;
+  const cp_shape& s = *shape;
+  if (final_out != nullptr && final_dtype != CP_BF16 && final_dtype != CP_FP32)
+    return CP_ERR_UNSUPPORTED;
+  if (s.batch != 1 || !mfma_prefill_applies(s) || prefill_mfma_splits_kv(s))
+    return CP_ERR_UNSUPPORTED;
+  if (s.total_q > 0 && (q == nullptr || q_pos == nullptr || acc_out == nullptr || acc_lse == nullptr))
+    return CP_ERR_NULL;
+  if (s.total_q > 0 && s.total_kv > 0 && (k == nullptr || v == nullptr || kv_pos == nullptr))
+    return CP_ERR_NULL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(acc_out) || !aligned16(final_out))
+    return CP_ERR_ALIGN;
+  if (s.total_q == 0) return CP_OK;
+  const size_t need = prefill_mfma_workspace_bytes(s);
+  if (need > 0 && (workspace == nullptr || !aligned256(workspace) || workspace_bytes < need))
+    return CP_ERR_WORKSPACE;
+  const PrefillAccumulate acc = {acc_out, acc_lse, final_out, final_lse, final_dtype};
+  return launch_prefill_mfma(s, resolve_scale(s.softmax_scale, s.head_dim), q, k, v, q_pos, kv_pos,
+                             nullptr, nullptr, CP_FP32, workspace, workspace_bytes, nullptr,
+                             nullptr, (hipStream_t)stream, &acc);
+}
+
 int cp_attn_decode(const cp_shape* shape, const void* q, const void* k, const void* v,
                    const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_kv,
                    const int32_t* bid, void* out, float* lse, int32_t out_dtype,
@@ -192,7 +220,9 @@ int cp_attn_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* c
 static int check_ring(const cp_ring_desc* d, bool decode) {
   if (d == nullptr) return CP_ERR_NULL;
   if (d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS) return CP_ERR_SHAPE;
-  if (d->reserved != 0) return CP_ERR_SHAPE;
+  if (d->fused_merge != 0 && d->fused_merge != 1) return CP_ERR_SHAPE;
+  if (d->fused_merge && (decode || d->keep_partials || d->part_dtype != CP_FP32))
+    return CP_ERR_UNSUPPORTED;
   if (d->n_q == nullptr || d->n_kv == nullptr || d->q == nullptr || d->k == nullptr ||
       d->v == nullptr || d->q_pos == nullptr || d->kv_pos == nullptr || d->out == nullptr)
     return CP_ERR_NULL;
@@ -305,14 +335,16 @@ int ring_prepare(const cp_ring_desc* d, bool decode, hipStream_t st, RingWork& w
   }
   w.call_ws = (char*)d->workspace + off;
   w.call_ws_bytes = d->workspace_bytes >= off ? d->workspace_bytes - off : 0;
-  // Two streams only when no call touches the shared per-call scratch.
-  if (d->aux_stream != nullptr && !decode && w.use_bounds) {
-    bool scratch = false;
+  // Two streams, and the merge fused into the epilogues, only when no call splits its KV axis
+  // through the shared per-call scratch.
+  bool scratch = !w.use_bounds;
+  if (!decode && w.use_bounds && (d->aux_stream != nullptr || d->fused_merge)) {
     for (int a = 0; a < d->n_ranks && !scratch; ++a)
-      for (int b = 0; b < d->n_ranks && !scratch; ++b) {
-        const cp_shape s = ring_shape(d, a, b, false);
-        scratch = prefill_mfma_workspace_bytes(s) > kv_tile_bounds_bytes(s.total_kv);
-      }
+      for (int b = 0; b < d->n_ranks && !scratch; ++b)
+        scratch = d->n_q[a] > 0 && prefill_mfma_splits_kv(ring_shape(d, a, b, false));
+  }
+  if (d->fused_merge && d->n_ranks > 1 && scratch) return CP_ERR_UNSUPPORTED;
+  if (d->aux_stream != nullptr && !decode && w.use_bounds && !d->fused_merge) {
     if (!scratch) {
       if (hipEventCreateWithFlags(&w.fork, hipEventDisableTiming) != hipSuccess) return CP_ERR_LAUNCH;
       if (hipEventCreateWithFlags(&w.join, hipEventDisableTiming) != hipSuccess) {
@@ -324,6 +356,26 @@ int ring_prepare(const cp_ring_desc* d, bool decode, hipStream_t st, RingWork& w
     }
   }
   return CP_OK;
+}
+
+// Fused merge: the N steps of one rank keep a running (O, LSE) in partial slot 0. Step 0
+// writes it, steps 1 .. N-2 merge into it in their epilogues, the last step writes the merged
+// O to the rank's output. `kv_of_step(j)` names the KV rank of step j.
+template <typename KvOf>
+int ring_rank_fused(const cp_ring_desc* d, const RingWork& w, const RingSlots& slots, int a,
+                    int n, hipStream_t st, KvOf kv_of_step) {
+  float* const acc_o = (float*)slots.out(0);
+  float* const acc_l = slots.lse(0);
+  float* const lse_out = d->lse != nullptr ? d->lse[a] : nullptr;
+  if (d->n_q[a] == 0) return CP_OK;
+  int rc = ring_partial(d, w, false, a, kv_of_step(0), acc_o, acc_l, st);
+  for (int j = 1; j < n && rc == CP_OK; ++j) {
+    const bool last = j == n - 1;
+    const PrefillAccumulate acc = {acc_o, acc_l, last ? d->out[a] : nullptr,
+                                   last ? lse_out : nullptr, d->out_dtype};
+    rc = ring_partial(d, w, false, a, kv_of_step(j), nullptr, nullptr, st, &acc);
+  }
+  return rc;
 }
 
 void ring_finish(RingWork& w) {
@@ -358,8 +410,9 @@ int ring_rank_steps(const RingWork& w, int n, hipStream_t st, Call call) {
 
 // One partial-attention call of the ring: queries of rank `a` against KV of rank `b`.
 int ring_partial(const cp_ring_desc* d, const RingWork& w, bool decode, int a, int b, void* o,
-                 float* l, hipStream_t st) {
+                 float* l, hipStream_t st, const PrefillAccumulate* acc = nullptr) {
   cp_shape s = ring_shape(d, a, b, decode);
+  if (acc != nullptr && (decode || !w.use_bounds)) return CP_ERR_UNSUPPORTED;
   if (decode)
     return cp_attn_decode(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b],
                           d->cu_seqlens_kv[b], d->bid[a], o, l, d->part_dtype, w.call_ws,
@@ -368,7 +421,8 @@ int ring_partial(const cp_ring_desc* d, const RingWork& w, bool decode, int a, i
     if (!aligned16(d->q[a]) || !aligned16(d->k[b]) || !aligned16(d->v[b])) return CP_ERR_ALIGN;
     return launch_prefill_mfma(s, resolve_scale(s.softmax_scale, s.head_dim), d->q[a], d->k[b],
                                d->v[b], d->q_pos[a], d->kv_pos[b], o, l, d->part_dtype, w.call_ws,
-                               w.call_ws_bytes, (char*)d->workspace + w.bounds_off[b], nullptr, st);
+                               w.call_ws_bytes, (char*)d->workspace + w.bounds_off[b], nullptr, st,
+                               acc);
   }
   return cp_attn_partial(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b], nullptr,
                          nullptr, o, l, d->part_dtype, w.call_ws, w.call_ws_bytes, st);
@@ -402,6 +456,10 @@ int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
   if (rc != CP_OK) return rc;
   // Algorithm 2 as seen from each rank k in turn: N ring steps, then a local merge.
   for (int k = 0; k < n && rc == CP_OK; ++k) {
+    if (d->fused_merge && n > 1) {
+      rc = ring_rank_fused(d, w, slots, k, n, st, [&](int j) { return ((k - j) % n + n) % n; });
+      continue;
+    }
     const int64_t base = d->keep_partials ? (int64_t)k * n : 0;
     rc = ring_rank_steps(w, n, st, [&](int j, hipStream_t sj) {
       const int s = ((k - j) % n + n) % n;  // origin rank of the KV held at step j
@@ -439,6 +497,10 @@ static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
   // (for each s the holders k = s, s+1, ... in ring order), so that the N partials of
   // one source are complete, and can be merged, before the slots are reused.
   for (int s = 0; s < n && rc == CP_OK; ++s) {
+    if (d->fused_merge && n > 1) {
+      rc = ring_rank_fused(d, w, slots, s, n, st, [&](int j) { return (s + j) % n; });
+      continue;
+    }
     rc = ring_rank_steps(w, n, st, [&](int j, hipStream_t sj) {
       const int k = (s + j) % n;
       return ring_partial(d, w, decode, s, k, slots.out(k), slots.lse(k), sj);

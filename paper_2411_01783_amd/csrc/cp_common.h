@@ -49,10 +49,23 @@ size_t prefill_mfma_workspace_bytes(const cp_shape& s);
 size_t kv_tile_bounds_bytes(int64_t total_kv);
 int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_out,
                           hipStream_t stream);
+// `acc`, when not NULL, turns the launch into "merge into a running result": out / lse /
+// out_dtype are ignored, (acc->out, acc->lse) are read and updated (Equation 4), and if
+// acc->final_out is not NULL the merged O goes there in acc->final_dtype instead of back to
+// acc->out. Only for launches that do not split the KV axis and are not packed batches.
+struct PrefillAccumulate {
+  float* out;        // fp32 [total_q, n_q_heads, head_dim]
+  float* lse;        // fp32 [total_q, n_q_heads]
+  void* final_out;   // or NULL
+  float* final_lse;  // or NULL
+  int32_t final_dtype;
+};
+bool prefill_mfma_splits_kv(const cp_shape& s);
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
-                        const void* tile_bounds, const int32_t* q_lo, hipStream_t stream);
+                        const void* tile_bounds, const int32_t* q_lo, hipStream_t stream,
+                        const PrefillAccumulate* acc = nullptr);
 
 // Packed batches on the MFMA path: per-sequence position ranges (see cp_varseq.hip).
 struct VarseqLayout {

@@ -55,7 +55,10 @@ struct Params {
   const int32_t* q_lo;    // BAND only: smallest visible key position per query token
   const int2* bounds;     // [n_tiles] (min, max) of kv_pos per tile
   void* out;              // final output (n_splits == 1)
-  float* lse;
+  float* lse;             // LSE output; ACC: the running LSE, read and written
+  float* acc;             // ACC: running O, fp32 [rows_all_heads][D]
+  void* final_out;        // ACC: where the merged O goes on the last step (else NULL)
+  float* final_lse;       // ACC: optional copy of the merged LSE
   float* part_out;        // split scratch [n_splits][total_q * n_q_heads][D] fp32
   float* part_lse;        // [n_splits][total_q * n_q_heads]
   int64_t rows;           // R = total_q * G
@@ -162,11 +165,15 @@ int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_
   return check_launch();
 }
 
+bool prefill_mfma_splits_kv(const cp_shape& s) { return make_plan(s).n_splits > 1; }
+
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
-                        const void* tile_bounds, const int32_t* q_lo, hipStream_t stream) {
+                        const void* tile_bounds, const int32_t* q_lo, hipStream_t stream,
+                        const PrefillAccumulate* acc) {
   const Plan pl = make_plan(s);
+  if (acc != nullptr && (pl.n_splits > 1 || q_lo != nullptr)) return CP_ERR_UNSUPPORTED;
   if (workspace_bytes < pl.bounds_bytes + pl.part_out_bytes + pl.part_lse_bytes)
     return CP_ERR_WORKSPACE;
   if (pl.n_row_blocks == 0) return CP_OK;
@@ -179,6 +186,11 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
   p.q_pos = q_pos; p.kv_pos = kv_pos; p.q_lo = q_lo;
   p.bounds = tile_bounds != nullptr ? (const int2*)tile_bounds : (const int2*)ws;
   p.out = out; p.lse = lse;
+  p.acc = nullptr; p.final_out = nullptr; p.final_lse = nullptr;
+  if (acc != nullptr) {
+    p.out = nullptr; p.lse = acc->lse; p.acc = acc->out;
+    p.final_out = acc->final_out; p.final_lse = acc->final_lse;
+  }
   p.part_out = (float*)(ws + pl.bounds_bytes);
   p.part_lse = (float*)(ws + pl.bounds_bytes + pl.part_out_bytes);
   p.group = s.n_q_heads / s.n_kv_heads;
@@ -197,7 +209,11 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
   const dim3 grid(pl.n_row_blocks, s.n_kv_heads, pl.n_splits);
   const bool direct_bf16 = pl.n_splits == 1 && out_dtype == CP_BF16;
   const bool band = q_lo != nullptr;
-  auto kern = pl.n_splits > 1
+  auto kern = acc != nullptr
+                  ? (acc->final_out != nullptr && acc->final_dtype == CP_BF16
+                         ? prefill_mfma_kernel<bf16_t, false, false, true>
+                         : prefill_mfma_kernel<float, false, false, true>)
+              : pl.n_splits > 1
                   ? (band ? prefill_mfma_kernel<float, true, true> : prefill_mfma_kernel<float, false, true>)
                   : direct_bf16
                         ? (band ? prefill_mfma_kernel<bf16_t, true, false>

@@ -311,7 +311,9 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
 // BAND: packed batch. Positions are shifted per sequence and a query also has a lower bound
 // q_lo (the shift of its sequence): visible iff q_lo <= kv_pos <= q_pos.
 // SPLIT: the launch splits the KV axis over grid.z and writes fp32 partials to the workspace.
-template <typename TO, bool BAND, bool SPLIT>
+// ACC: the result is merged into a running (O, LSE) in the epilogue instead of being written
+// as a partial (Equation 4 applied step by step); see the epilogue.
+template <typename TO, bool BAND, bool SPLIT, bool ACC = false>
 __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     Params p, const int2* __restrict__ tile_bounds) {
   extern __shared__ __align__(16) char smem[];
@@ -610,13 +612,35 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   }
 
   // ---- epilogue ----
+  static_assert(!(ACC && SPLIT), "the running result is merged by unsplit launches only");
   const float l_tot = R.l_run + xor32(R.l_run);
-  const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+  float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
   const float lse_val =
       l_tot > 0.f ? (R.m_run + __builtin_amdgcn_logf(l_tot)) * kLn2 : -INFINITY;
   constexpr bool direct = !SPLIT;
-  float* const lse_dst = direct ? p.lse : p.part_lse + (int64_t)split * p.rows_all_heads;
-  if (row_ok && g == 0) lse_dst[row_lin] = lse_val;
+  // ACC: weights of Equation 4 for the pair (running result, this step). a_old scales the
+  // stored row, the step's row is scaled on its way into the staging buffer. A row the step
+  // saw nothing of keeps its stored value (a_old = 1, nothing staged): it is not touched at
+  // all unless this is the step that writes the final output.
+  float a_old = 0.f;
+  if (ACC) {
+    const float lse_old = row_ok ? p.lse[row_lin] : -INFINITY;
+    const float m = fmaxf(lse_old, lse_val);
+    const float w_old = m == -INFINITY ? 0.f : __expf(lse_old - m);
+    const float w_cur = m == -INFINITY ? 0.f : __expf(lse_val - m);
+    const float den = w_old + w_cur;
+    const float rden = den > 0.f ? 1.f / den : 0.f;
+    a_old = l_tot > 0.f ? w_old * rden : 1.f;
+    inv *= w_cur * rden;
+    const float lse_new = den > 0.f ? m + __logf(den) : -INFINITY;
+    if (row_ok && g == 0) {
+      if (l_tot > 0.f) p.lse[row_lin] = lse_new;
+      if (p.final_lse != nullptr) p.final_lse[row_lin] = lse_new;
+    }
+  } else {
+    float* const lse_dst = direct ? p.lse : p.part_lse + (int64_t)split * p.rows_all_heads;
+    if (row_ok && g == 0) lse_dst[row_lin] = lse_val;
+  }
 
   // Transpose through LDS (the tile buffers are dead once every wavefront has left the walk;
   // each wavefront then uses a private region). Accumulator (db, i) of lane (n, g) is channel
@@ -634,15 +658,48 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     }
   wave_lds_fence();
   const int64_t r0 = (int64_t)row_block * BM + wave * 32;
-  if (direct && sizeof(TO) == 2) {
+  const bool to_final = !ACC || p.final_out != nullptr;  // uniform
+  if (ACC && !to_final) {
+    // running result updated in place, 2 rows per pass; rows the step did not see are skipped
+    float* const o = p.acc;
+    const bool seen = l_tot > 0.f;
+#pragma unroll
+    for (int pass = 0; pass < 16; ++pass) {
+      const int rr = pass * 2 + (lane >> 5), c = (lane & 31) * 4;
+      const int64_t rl = __shfl(row_lin, rr, 64);
+      const float ao = __shfl(a_old, rr, 64);
+      const bool touch = __shfl((int)seen, rr, 64) != 0 && r0 + rr < p.rows;
+      floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      if (touch) {
+        if (ao != 0.f) {
+          const floatx4_t old = *(const floatx4_t*)(o + rl * D + c);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) a[x] = fmaf(ao, old[x], a[x]);
+        }
+        *(floatx4_t*)(o + rl * D + c) = a;
+      }
+    }
+  } else if (direct && sizeof(TO) == 2) {
     // 4 rows per pass: 16 lanes x 8 channels each
-    bf16_t* const o = (bf16_t*)p.out;
+    bf16_t* const o = (bf16_t*)(ACC ? p.final_out : p.out);
 #pragma unroll
     for (int pass = 0; pass < 8; ++pass) {
       const int rr = pass * 4 + (lane >> 4), c = (lane & 15) * 8;
       const int64_t rl = __shfl(row_lin, rr, 64);
-      const floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
-      const floatx4_t b = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4 + 16);
+      floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      floatx4_t b = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4 + 16);
+      if (ACC) {
+        const float ao = __shfl(a_old, rr, 64);
+        if (ao != 0.f && r0 + rr < p.rows) {
+          const floatx4_t oa = *(const floatx4_t*)(p.acc + rl * D + c);
+          const floatx4_t ob = *(const floatx4_t*)(p.acc + rl * D + c + 4);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            a[x] = fmaf(ao, oa[x], a[x]);
+            b[x] = fmaf(ao, ob[x], b[x]);
+          }
+        }
+      }
       bf16x8_t w;
 #pragma unroll
       for (int x = 0; x < 4; ++x) {
@@ -653,13 +710,22 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     }
   } else {
     // 2 rows per pass: 32 lanes x 4 channels each
-    float* const o =
-        direct ? (float*)p.out : p.part_out + (int64_t)split * p.rows_all_heads * D;
+    float* const o = ACC ? (float*)p.final_out
+                         : direct ? (float*)p.out
+                                  : p.part_out + (int64_t)split * p.rows_all_heads * D;
 #pragma unroll
     for (int pass = 0; pass < 16; ++pass) {
       const int rr = pass * 2 + (lane >> 5), c = (lane & 31) * 4;
       const int64_t rl = __shfl(row_lin, rr, 64);
-      const floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      floatx4_t a = *(const floatx4_t*)(stage + rr * OUT_STRIDE + c * 4);
+      if (ACC) {
+        const float ao = __shfl(a_old, rr, 64);
+        if (ao != 0.f && r0 + rr < p.rows) {
+          const floatx4_t old = *(const floatx4_t*)(p.acc + rl * D + c);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) a[x] = fmaf(ao, old[x], a[x]);
+        }
+      }
       if (r0 + rr < p.rows) *(floatx4_t*)(o + rl * D + c) = a;
     }
   }

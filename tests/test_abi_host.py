@@ -30,6 +30,22 @@ def test_every_declared_symbol_is_exported(lib):
         assert hasattr(lib, name), name
 
 
+def test_partial_accumulate_rejects_what_it_cannot_run(lib):
+    import ctypes
+    one = ctypes.c_void_p(256)  # never dereferenced: every call below fails validation first
+    def call(shape):
+        return lib.cp_attn_partial_accumulate(ctypes.byref(shape), one, one, one, one, one, one, one,
+                                              None, 0, None, one, ctypes.c_size_t(1 << 30), None)
+    # fp32 inputs, head_dim 64, a packed batch, and a query shard short enough to split the KV axis
+    assert call(B.make_shape(B.CP_FP32, 128, 16, 1, 4096, 4096)) == -3
+    assert call(B.make_shape(B.CP_BF16, 64, 16, 1, 4096, 4096)) == -3
+    assert call(B.make_shape(B.CP_BF16, 128, 16, 1, 4096, 4096, batch=2)) == -3
+    assert call(B.make_shape(B.CP_BF16, 128, 16, 1, 64, 4096)) == -3
+    ok_shape = B.make_shape(B.CP_BF16, 128, 16, 1, 4096, 4096)
+    assert lib.cp_attn_partial_accumulate(ctypes.byref(ok_shape), one, one, one, one, one, None, one,
+                                          None, 0, None, one, ctypes.c_size_t(1 << 30), None) == -1
+
+
 def test_probe_rejects_bad_arguments_before_any_launch(lib):
     import ctypes
     flop = ctypes.c_double(0.0)

@@ -214,6 +214,33 @@ def test_mfma_partial_score_spikes(oracle, causal, tq):
                                np.broadcast_to(v64[464], (int(sees_big.sum()), 16, 128)), atol=1e-2)
 
 
+def test_ring_fused_merge_matches_unsharded(oracle):
+    # the drivers' fused-merge option (running result in the epilogues, no partials, no merge
+    # pass) in both ring orders; t = 16384 keeps every call unsplit, which the option needs
+    n, t = 2, 16384
+    q, q64 = randn(41, (t, 16, 128))
+    k, k64 = randn(42, (t, 1, 128))
+    v, v64 = randn(43, (t, 1, 128))
+    pos = [B.cp_shard_positions(t, n, r) for r in range(n)]
+    rows = np.r_[0:64, 4090:4102, 8190:8200, 12280:12296, t - 64:t]  # oracle on a sample of rows
+    ref_o, ref_l = oracle.attn(q64[rows], k64, v64, rows, np.arange(t))
+    where = {int(p): (a, i) for a in range(n) for i, p in enumerate(pos[a])}
+    for order in (B.cp_ring_passkv, B.cp_ring_passq):
+        ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                      [i32(p) for p in pos], [i32(p) for p in pos], out_dtype=torch.float32,
+                      fused_merge=True)
+        assert ring.partial_out.shape[0] == 1
+        out, lse = order(ring)
+        torch.cuda.synchronize()
+        got_o = torch.stack([out[where[int(r)][0]][where[int(r)][1]] for r in rows])
+        got_l = torch.stack([lse[where[int(r)][0]][where[int(r)][1]] for r in rows])
+        check(got_o, got_l, ref_o, ref_l, what=order.__name__)
+    small = B.Ring([dev(q[p][:64]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                   [i32(p[:64]) for p in pos], [i32(p) for p in pos], fused_merge=True)
+    with pytest.raises(B.CpError):  # short query shards split the KV axis: not supported
+        B.cp_ring_passkv(small)
+
+
 @pytest.mark.parametrize("n,t,two_streams", [(4, 2048, False), (3, 1000, False),
                                              (4, 2048, True), (2, 16384, True)])
 def test_mfma_load_balanced_partials_and_merge(oracle, n, t, two_streams):
@@ -264,6 +291,45 @@ def test_ring_passkv_bf16_partials(oracle):
         check(out[a], lse[a], ref_o[pos[a]], ref_l[pos[a]], what="merged rank %d" % a)
     po, pl = oracle.attn(q64[pos[3]], k64[pos[1]], v64[pos[1]], pos[3], pos[1])
     check(*ring.partial(3, 1), po, pl, what="bf16 partial 3,1")
+
+
+@pytest.mark.parametrize("final_dtype", [torch.float32, torch.bfloat16])
+def test_partial_accumulate_matches_attention_on_the_union(oracle, final_dtype):
+    # three steps merged in the kernel's epilogue == attention over the three KV sets together
+    tq, nkv = 2048, 3
+    q, q64 = randn(61, (tq, 16, 128))
+    rng = np.random.default_rng(62)
+    qp = rng.integers(0, 1500, size=tq)
+    qp[:5] = -1            # padded queries: see nothing in any step
+    qp[5:40] = 700         # see all of step 0, part of step 1, nothing of step 2
+    ks, vs, kps = [], [], []
+    for i in range(nkv):
+        n_k = (300, 421, 256)[i]
+        k, _ = randn(63 + i, (n_k, 1, 128))
+        v, _ = randn(73 + i, (n_k, 1, 128))
+        ks.append(k); vs.append(v)
+        kps.append(rng.permutation(500)[:n_k] + 500 * i)
+    acc_o = torch.empty((tq, 16, 128), dtype=torch.float32, device="cuda")
+    acc_l = torch.empty((tq, 16), dtype=torch.float32, device="cuda")
+    fin_o = torch.empty((tq, 16, 128), dtype=final_dtype, device="cuda")
+    fin_l = torch.empty((tq, 16), dtype=torch.float32, device="cuda")
+    dq, dqp = dev(q), i32(qp)
+    B.cp_attn_partial(dq, dev(ks[0]), dev(vs[0]), dqp, i32(kps[0]), out=acc_o, lse=acc_l)
+    B.cp_attn_partial_accumulate(dq, dev(ks[1]), dev(vs[1]), dqp, i32(kps[1]), acc_o, acc_l)
+    torch.cuda.synchronize()
+    ref2 = oracle.attn(q64, np.concatenate([W.to_f64(x) for x in ks[:2]]),
+                       np.concatenate([W.to_f64(x) for x in vs[:2]]), qp, np.concatenate(kps[:2]))
+    check(acc_o, acc_l, *ref2, what="running result after two steps")
+    before = acc_o.clone()
+    B.cp_attn_partial_accumulate(dq, dev(ks[2]), dev(vs[2]), dqp, i32(kps[2]), acc_o, acc_l,
+                                 final_out=fin_o, final_lse=fin_l)
+    torch.cuda.synchronize()
+    ref3 = oracle.attn(q64, np.concatenate([W.to_f64(x) for x in ks]),
+                       np.concatenate([W.to_f64(x) for x in vs]), qp, np.concatenate(kps))
+    check(fin_o, fin_l, *ref3, what="final output")
+    check(fin_o, acc_l, *ref3, what="running LSE after the last step")
+    assert torch.equal(acc_o, before)  # the last step writes the final output only
+    assert np.isneginf(ref3[1][:5]).all() and not np.isneginf(ref3[1][5:]).any()
 
 
 def test_mfma_split_kv_short_query_shard(oracle):
