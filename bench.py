@@ -3,12 +3,14 @@
 
 One "step" is one pass of the whole hot path over one batch of synthetic input: for the
 default workload (Llama3-405B per-GPU head shape, 128K full prefill, pass-KV) that is the
-complete ring of Algorithm 2 over all 16 virtual CP ranks: 16 x (16 partial-attention calls
-on load-balanced shards + 1 merge). Inputs are resident in HBM before the timed region.
+complete ring of Algorithm 2 over all 16 virtual CP ranks: 16 x 16 partial-attention calls
+on load-balanced shards, each merging its result into the rank's running (O, LSE) in its
+epilogue (Equation 4; `aux` also times the variant with 16 stored partials and a separate
+merge kernel per rank). Inputs are resident in HBM before the timed region.
 
 Prints ONE JSON line. `value` is causal-effective TFLOP/s (4 * d * N_H * visible pairs).
 `roofline` describes the dominant kernel (the bf16 MFMA partial-attention kernel), timed
-with HIP events around every partial-attention call in a second pass over the same ring.
+with HIP events around the plain partial-attention calls of every rank in a second pass.
 `cpu_baseline` times the fp64 oracle on a bounded sample of the same workload.
 `aux` carries the bandwidth-bound parts (merge, split-KV decode) in GB/s.
 """
@@ -57,10 +59,13 @@ def build_prefill(w: W.Workload):
     vs = [v[i].contiguous() for i in idx]
     del q
     ps = [_i32(p) for p in pos]
-    # one stream: with the drivers' optional second stream consecutive launches overlap, which
-    # gains under 1 % here and makes per-kernel durations in a trace meaningless
-    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
-    return dict(ring=ring, pos=pos, qs=qs, ks=ks, vs=vs, ps=ps, k_full=k, v_full=v)
+    # The merge (Equation 4) runs in the attention epilogues: one running fp32 (O, LSE) per rank.
+    # One stream: with the drivers' optional second stream consecutive launches overlap, which
+    # gains under 1 % here and makes per-kernel durations in a trace meaningless.
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, fused_merge=True)
+    # scratch for the per-call measurements: 16 fp32 partials and their separate merge
+    parts = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
+    return dict(ring=ring, parts=parts, pos=pos, qs=qs, ks=ks, vs=vs, ps=ps, k_full=k, v_full=v)
 
 
 def time_steps(fn, steps: int, warmup: int) -> float:
@@ -80,7 +85,7 @@ def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
     One event pair brackets the n back-to-back launches of a rank's loop (events between
     the launches would add a dispatch gap to every one of them), a second pair the merge."""
     n = w.n_ranks
-    ring = st["ring"]
+    ring = st["parts"]
     total_ms, total_flop, n_launch = 0.0, 0.0, 0
     merge_ms, merge_bytes = 0.0, 0.0
     ws = ring.workspace
@@ -115,7 +120,7 @@ def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
 def per_call_prefill(w: W.Workload, st: dict, reps: int = 8):
     """One cp_attn_partial call at its real shape: an off-diagonal ring step (half of the
     query rows see the whole shard, the others nothing) and the diagonal step."""
-    ring = st["ring"]
+    ring = st["parts"]
     out = {}
     kq = w.n_ranks // 2
     for label, s in (("off_diagonal", (kq + 5) % w.n_ranks), ("diagonal", kq)):
@@ -355,7 +360,7 @@ def main():
     st = build_prefill(w)
     ring = st["ring"]
     if args.pmc_probe:
-        pmc_probe(ring)
+        pmc_probe(st["parts"])
         return
     sec = time_steps(lambda: B.cp_ring_passkv(ring), args.steps, args.warmup)
     t = w.t_new
@@ -371,7 +376,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "order": "pass-KV", "virtual_ranks": w.n_ranks,
                    "tokens": t, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "head_dim": w.head_dim, "partial_dtype": "fp32",
+                   "head_dim": w.head_dim, "merge": "in the attention epilogues, fp32 running result",
                    "flops": "causal-effective 4*d*N_H*pairs",
                    "ms_per_rank": round(sec * 1e3 / w.n_ranks, 3)},
         "frac_of_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
@@ -390,11 +395,17 @@ def main():
     if not args.no_aux and w.name == "prefill_128k":
         # the same ring with bf16 partial outputs (the width the paper's All2All model assumes);
         # the headline keeps fp32 partials
+        parts = st["parts"]
+        secp = time_steps(lambda: B.cp_ring_passkv(parts), args.steps, args.warmup)
+        result["aux"]["ring_separate_merge_fp32_partials"] = {
+            "tflops": round(flop_step / secp / 1e12, 2),
+            "ms_per_rank": round(secp * 1e3 / w.n_ranks, 3)}
         ring16 = B.Ring(st["qs"], st["ks"], st["vs"], st["ps"], st["ps"], out_dtype=torch.bfloat16,
                         part_dtype=torch.bfloat16)
         sec16 = time_steps(lambda: B.cp_ring_passkv(ring16), args.steps, args.warmup)
-        result["aux"]["ring_bf16_partials"] = {"tflops": round(flop_step / sec16 / 1e12, 2),
-                                               "ms_per_rank": round(sec16 * 1e3 / w.n_ranks, 3)}
+        result["aux"]["ring_separate_merge_bf16_partials"] = {
+            "tflops": round(flop_step / sec16 / 1e12, 2),
+            "ms_per_rank": round(sec16 * 1e3 / w.n_ranks, 3)}
         del ring16
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline_prefill(w, st)

@@ -35,12 +35,16 @@ def _shard(w, q, k, v):
         [v[i].contiguous() for i in idx]
 
 
-def test_prefill_128k_passkv_ring_sampled(oracle):
+@pytest.mark.parametrize("fused_merge", [True, False])
+def test_prefill_128k_passkv_ring_sampled(oracle, fused_merge):
+    # fused_merge=True is the configuration bench.py times; False keeps 16 partials per rank
+    # and merges them with the merge kernel
     w = W.WORKLOADS["prefill_128k"]
     q, k, v = W.qkv(w, device="cuda")
     pos, qs, ks, vs = _shard(w, q, k, v)
     ps = [i32(p) for p in pos]
-    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32,
+                  fused_merge=fused_merge)
     out, lse = B.cp_ring_passkv(ring)
     torch.cuda.synchronize()
     k64, v64 = W.to_f64(k), W.to_f64(v)
