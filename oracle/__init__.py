@@ -5,9 +5,11 @@ benchmark's CPU-baseline leg. The product path never imports this package and
 this package never imports the product.
 """
 from .cp_oracle import (  # noqa: F401
+    KVCache,
     attn,
     build,
     chunk_bounds,
+    decode_owner,
     merge,
     num_threads,
     ring_passkv,

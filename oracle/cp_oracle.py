@@ -16,6 +16,11 @@ bookkeeping that follows the paper's own steps:
                              query's source rank (the All2All) before merging.
 * `ring_passq_decode`      - Algorithm 4 (batched ring pass-Q decode) with the
                              batch ids travelling with the queries.
+* `KVCache`                - the persistent per-rank KV cache of multi-turn
+                             inference (Sections 3.5.2, 3.6): every turn's new
+                             K/V, decode tokens included, are appended to the
+                             owning rank's share; `decode_owner` is Section
+                             3.6's round-robin placement.
 * `select_order`           - pass-KV / pass-Q choice (Section 3.3 Algorithm 1,
                              Appendix C Algorithm 5, Appendix D) from the roofline
                              latencies of Table 1, not from the rearranged tests.
@@ -246,6 +251,62 @@ def shard_decode_batch(lengths: Sequence[int], n_ranks: int, decode_iter: int = 
                           q_pos=np.asarray(qp, dtype=np.int32)))
     assert sum(len(r["bid"]) for r in ranks) == n_seq
     return ranks
+
+
+# --------------------------------------------------------------------------
+# Persistent KV cache across turns (Sections 3.5.2 and 3.6)
+# --------------------------------------------------------------------------
+
+def decode_owner(seq: int, decode_iter: int, n_ranks: int) -> int:
+    """Rank that takes sequence `seq`'s token at decode iteration `decode_iter` (Section 3.6:
+    the batch is dealt round-robin and the deal moves on by one rank per iteration, so that
+    no rank's cache grows faster than the others')."""
+    return (seq + decode_iter) % n_ranks
+
+
+class KVCache:
+    """One rank's share of the KV cache for a batch of sequences, as plain per-sequence lists.
+
+    Sequence b may hold at most capacity[b] tokens on this rank. `append` adds tokens of one
+    sequence in order and drops (and counts) what does not fit. `packed()` lays the cache
+    out as the attention functions take it: sequence b owns capacity[b] consecutive slots,
+    tokens first, the unused rest carrying position INT32_MAX (never visible) and zeros.
+    """
+
+    def __init__(self, capacity: Sequence[int], n_kv_heads: int, head_dim: int):
+        self.capacity = [int(c) for c in capacity]
+        self.shape = (n_kv_heads, head_dim)
+        self.k = [[] for _ in self.capacity]
+        self.v = [[] for _ in self.capacity]
+        self.pos = [[] for _ in self.capacity]
+        self.dropped = 0
+
+    def append(self, seq: int, k_new, v_new, pos_new) -> None:
+        k_new = np.asarray(k_new, dtype=np.float64)
+        v_new = np.asarray(v_new, dtype=np.float64)
+        for i, p in enumerate(np.asarray(pos_new, dtype=np.int64)):
+            if len(self.pos[seq]) >= self.capacity[seq]:
+                self.dropped += 1
+                continue
+            self.k[seq].append(k_new[i].reshape(self.shape))
+            self.v[seq].append(v_new[i].reshape(self.shape))
+            self.pos[seq].append(int(p))
+
+    def used(self) -> np.ndarray:
+        return np.asarray([len(p) for p in self.pos], dtype=np.int32)
+
+    def packed(self):
+        """(k, v, kv_pos, cu_kv) with cu_kv the capacity bounds."""
+        cu = np.concatenate([[0], np.cumsum(self.capacity)]).astype(np.int32)
+        k = np.zeros((int(cu[-1]),) + self.shape)
+        v = np.zeros_like(k)
+        pos = np.full(int(cu[-1]), INT32_MAX, dtype=np.int32)
+        for b in range(len(self.capacity)):
+            for j in range(len(self.pos[b])):
+                k[cu[b] + j] = self.k[b][j]
+                v[cu[b] + j] = self.v[b][j]
+                pos[cu[b] + j] = self.pos[b][j]
+        return k, v, pos, cu
 
 
 # --------------------------------------------------------------------------

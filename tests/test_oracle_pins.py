@@ -417,6 +417,124 @@ def test_batched_decode_is_independent_of_owner_rank(oracle, decode_iter):
 
 
 # ---------------------------------------------------------------------------
+# persistent KV cache over several turns (Sections 3.5.2, 3.6)
+# ---------------------------------------------------------------------------
+
+def test_round_robin_decode_placement_keeps_the_caches_level(oracle):
+    # over N consecutive iterations every rank takes each sequence's token exactly once, and
+    # within one iteration a batch that is a multiple of N is dealt evenly
+    for n in (1, 2, 4, 16):
+        for b in range(2 * n):
+            assert sorted(oracle.decode_owner(b, t, n) for t in range(5, 5 + n)) == list(range(n))
+        for t in range(3):
+            owners = [oracle.decode_owner(b, t, n) for b in range(2 * n)]
+            assert all(owners.count(r) == 2 for r in range(n))
+            ranks = oracle.shard_decode_batch([7] * (2 * n), n, t)
+            for r in range(n):
+                assert list(ranks[r]["bid"]) == [b for b in range(2 * n) if owners[b] == r]
+
+
+def test_kv_cache_capacity_and_padding(oracle):
+    c = oracle.KVCache([3, 0, 2], 1, 4)
+    c.append(0, rnd(1, 2, 1, 4), rnd(2, 2, 1, 4), [5, 9])
+    c.append(2, rnd(3, 3, 1, 4), rnd(4, 3, 1, 4), [0, 1, 2])   # third token does not fit
+    c.append(1, rnd(5, 1, 1, 4), rnd(6, 1, 1, 4), [0])          # no room at all
+    assert c.dropped == 2 and list(c.used()) == [2, 0, 2]
+    k, v, pos, cu = c.packed()
+    assert list(cu) == [0, 3, 3, 5]
+    assert list(pos) == [5, 9, oracle.cp_oracle.INT32_MAX, 0, 1]
+    np.testing.assert_array_equal(k[0:2], rnd(1, 2, 1, 4))
+    np.testing.assert_array_equal(v[3:5], rnd(4, 3, 1, 4)[:2])
+    # an unused slot is seen by no query, however late its position
+    q = rnd(7, 1, 2, 4)
+    o_pad, l_pad = oracle.attn(q, k[0:3], v[0:3], [2 ** 31 - 2], pos[0:3])
+    o_ref, l_ref = oracle.attn(q, k[0:2], v[0:2], [2 ** 31 - 2], pos[0:2])
+    np.testing.assert_array_equal(o_pad, o_ref)
+    np.testing.assert_array_equal(l_pad, l_ref)
+
+
+def test_multi_turn_replay_over_the_persistent_cache(oracle):
+    """Full prefill, decode steps, a partial prefill and another decode step, each turn
+    reading the cache the earlier turns left: every result equals causal attention over the
+    sequence's whole history (the exactness claims of Sections 3.5.1, 3.5.2 and 3.6)."""
+    n, nh, d = 3, 4, 8
+    first, second = [13, 6, 20, 1], [7, 12, 1, 5]
+    n_seq = len(first)
+    n_decode = n + 1
+    cap = [-(-(a + b) // n) + n_decode + 3 for a, b in zip(first, second)]
+    caches = [oracle.KVCache(cap, 1, d) for _ in range(n)]
+    total = [a + b + n_decode + 1 for a, b in zip(first, second)]
+    qs = [rnd(500 + b, total[b], nh, d) for b in range(n_seq)]
+    ks = [rnd(520 + b, total[b], 1, d) for b in range(n_seq)]
+    vs = [rnd(540 + b, total[b], 1, d) for b in range(n_seq)]
+    ref = [oracle.unsharded_causal(qs[b], ks[b], vs[b]) for b in range(n_seq)]
+    length = [0] * n_seq
+
+    def check_rows(b, pos, o, l):
+        np.testing.assert_allclose(o, ref[b][0][pos], atol=1e-12)
+        np.testing.assert_allclose(l, ref[b][1][pos], atol=1e-12)
+
+    def prefill_turn(b, t_new, order):
+        # this turn's K/V join the cache first (Algorithm 2 / 3 read KV_k = cache + new)
+        p0 = length[b]
+        qpos = [oracle.shard_positions(t_new, n, r, offset=p0) for r in range(n)]
+        for r in range(n):
+            caches[r].append(b, ks[b][qpos[r]], vs[b][qpos[r]], qpos[r])
+        views = []
+        for r in range(n):
+            k, v, pos, cu = caches[r].packed()
+            sl = slice(cu[b], cu[b + 1])       # unused slots included: they stay invisible
+            views.append((k[sl], v[sl], pos[sl]))
+        o, l, _, _ = order([qs[b][p] for p in qpos], [x[0] for x in views],
+                           [x[1] for x in views], qpos, [x[2] for x in views])
+        for r in range(n):
+            check_rows(b, qpos[r], o[r], l[r])
+        length[b] += t_new
+
+    def decode_turn(t):
+        bids = [[] for _ in range(n)]
+        for b in range(n_seq):
+            r = oracle.decode_owner(b, t, n)
+            p = length[b]
+            caches[r].append(b, ks[b][p:p + 1], vs[b][p:p + 1], [p])
+            bids[r].append(b)
+        packed = [c.packed() for c in caches]
+        o, l, _, _ = oracle.ring_passq_decode(
+            [qs_rows(bids[r]) for r in range(n)], bids,
+            [[length[b] for b in bids[r]] for r in range(n)],
+            [x[0] for x in packed], [x[1] for x in packed], [x[2] for x in packed],
+            [x[3] for x in packed])
+        for r in range(n):
+            for i, b in enumerate(bids[r]):
+                check_rows(b, [length[b]], o[r][i:i + 1], l[r][i:i + 1])
+        for b in range(n_seq):
+            length[b] += 1
+
+    def qs_rows(bs):
+        if not bs:
+            return np.zeros((0, nh, d))
+        return np.concatenate([qs[b][length[b]:length[b] + 1] for b in bs])
+
+    for b in range(n_seq):
+        prefill_turn(b, first[b], oracle.ring_passkv)
+    for t in range(n_decode):
+        decode_turn(t)
+    for b in range(n_seq):
+        prefill_turn(b, second[b], oracle.ring_passq if b % 2 else oracle.ring_passkv)
+    decode_turn(n_decode)
+    assert length == total
+    assert all(c.dropped == 0 for c in caches)
+    # every token of every sequence sits in exactly one rank's cache
+    for b in range(n_seq):
+        held = sorted(p for c in caches for p in c.pos[b])
+        assert held == list(range(total[b]))
+    # the decode tokens went round: no rank holds more than its share plus one of them
+    for b in range(n_seq):
+        dec = [sum(first[b] <= p < first[b] + n_decode for p in c.pos[b]) for c in caches]
+        assert max(dec) - min(dec) <= 1
+
+
+# ---------------------------------------------------------------------------
 # planted mistakes: each plausible slip in a re-implementation must trip a pin above
 # ---------------------------------------------------------------------------
 
