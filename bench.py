@@ -233,6 +233,35 @@ def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False):
 
 
 # ---------------------------------------------------------------------------
+# KV-cache append (aux; HBM-bound copy): one rank's share of a 128K prefill, then the
+# one-token appends of a decode step
+# ---------------------------------------------------------------------------
+
+def bench_kv_append(reps: int = 20):
+    w = W.WORKLOADS["prefill_128k"]
+    rows = w.t_new // w.n_ranks                      # 8192 tokens of one sequence per rank
+    k_new = W.normal(71, (rows, w.n_kv_heads, w.head_dim), w.dtype, "cuda")
+    v_new = W.normal(72, (rows, w.n_kv_heads, w.head_dim), w.dtype, "cuda")
+    pos = _i32(B.cp_shard_positions(w.t_new, w.n_ranks, 0))
+    cu_new = _i32([0, rows])
+    cache = B.KVCache([rows * (reps + 4)], w.n_kv_heads, w.head_dim)
+    sec = time_steps(lambda: B.cp_kv_append(cache, k_new, v_new, pos, cu_new), reps, 3)
+    moved = 2 * (2 * k_new.numel() * 2) + 2 * rows * 4          # K, V read + written; positions
+    res = {"prefill_rows": rows, "prefill_us": sec * 1e6, "prefill_gbs": moved / sec / 1e9}
+    # decode step: the owner of 2 of 32 sequences appends one token each
+    d = W.WORKLOADS["decode_b32"]
+    cache = B.KVCache([reps + 8] * d.batch, d.n_kv_heads, d.head_dim)
+    counts = np.zeros(d.batch, dtype=np.int64)
+    counts[[0, d.n_ranks]] = 1
+    cu_new = _i32(np.concatenate([[0], np.cumsum(counts)]))
+    sec = time_steps(lambda: B.cp_kv_append(cache, k_new[:2], v_new[:2], pos[:2], cu_new), reps, 3)
+    res["decode_step_us"] = sec * 1e6
+    torch.cuda.synchronize()
+    res["dropped"] = int(cache.dropped.item())
+    return {k: (round(v, 3) if isinstance(v, float) else v) for k, v in res.items()}
+
+
+# ---------------------------------------------------------------------------
 # persistent-KV partial prefill, pass-Q (aux; launch-bound at small T)
 # ---------------------------------------------------------------------------
 
@@ -419,6 +448,7 @@ def main():
         result["aux"]["partial_prefill"] = bench_partial_prefill(
             ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
              "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"])
+        result["aux"]["kv_append"] = bench_kv_append()
         result["aux"]["selector"] = selector_table(tflops * 1e12)
         result["aux"]["mfma_rate_probe"] = mfma_rate_probe()
     print(json.dumps(result))

@@ -319,6 +319,59 @@ int cp_select_order(const cp_select_params* params, int64_t t_new, int64_t p_cac
                     int32_t rule, int32_t* order_out);
 
 /*
+ * Persistent KV cache of one rank (Sections 3.5.2 and 3.6: the K/V of every turn's new tokens,
+ * decode tokens included, stay in the cache of the rank that owns them and are read by the
+ * later turns' partial prefill and decode).
+ *
+ * Layout, all device memory owned by the caller:
+ *   k_cache, v_cache  [slots, n_kv_heads, head_dim] in shape->dtype, 16-byte aligned
+ *   kv_pos_cache      int32 [slots]
+ *   cu_seqlens_kv     int32 [batch+1]: sequence b owns slots [cu[b], cu[b+1]), its capacity
+ *   seq_used          int32 [batch]: tokens held per sequence; they fill the front of the
+ *                     sequence's slot range in arrival order
+ * A slot that holds no token carries CP_POS_PAD_KV in kv_pos_cache, which no query position
+ * reaches: cp_attn_decode, cp_attn_partial and the ring drivers take the cache (or one
+ * sequence's slot range of it) as it is, with cu_seqlens_kv as the sequence boundaries.
+ *
+ * cp_kv_cache_reset marks every slot unused, clears K and V (an unused slot must not hold a
+ * NaN or Inf pattern: masked keys still enter the P V product with weight zero) and zeroes
+ * seq_used and *dropped (dropped may be NULL). It reads shape->dtype, head_dim, n_kv_heads,
+ * batch and total_kv (= slots). Errors: CP_ERR_NULL, CP_ERR_SHAPE (batch < 1, slots negative
+ * or > INT32_MAX), CP_ERR_UNSUPPORTED (dtype, head_dim), CP_ERR_ALIGN.
+ */
+int cp_kv_cache_reset(const cp_shape* shape, void* k_cache, void* v_cache,
+                      int32_t* kv_pos_cache, int32_t* seq_used, int32_t* dropped, void* stream);
+
+/*
+ * Append new tokens to the cache described above.
+ *   shape->dtype, head_dim, n_kv_heads  element type and row shape (n_q_heads is not used)
+ *   shape->batch    sequences in the cache;  shape->total_kv  slots
+ *   shape->total_q  number of new tokens in this call
+ *   k_new, v_new    (device) [total_q, n_kv_heads, head_dim], 16-byte aligned
+ *   pos_new         (device) int32 [total_q]
+ *   cu_seqlens_new  (device) int32 [batch+1]: the new tokens of sequence b are rows
+ *                   [cu_new[b], cu_new[b+1]); they go to slots cu_kv[b] + seq_used[b] + 0, 1, ...
+ *   seq_used        (device) read, then advanced by the number of tokens taken
+ *   dropped         (device) int32 or NULL: incremented by the number of tokens that did not
+ *                   fit their sequence's capacity (those are not stored)
+ * Two launches on `stream` (copy, then the update of seq_used); calls on one cache must be
+ * ordered by the caller (same stream or events).
+ * Errors: CP_ERR_NULL, CP_ERR_SHAPE, CP_ERR_UNSUPPORTED (dtype, head_dim), CP_ERR_ALIGN.
+ */
+int cp_kv_append(const cp_shape* shape, const void* k_new, const void* v_new,
+                 const int32_t* pos_new, const int32_t* cu_seqlens_new, void* k_cache,
+                 void* v_cache, int32_t* kv_pos_cache, const int32_t* cu_seqlens_kv,
+                 int32_t* seq_used, int32_t* dropped, void* stream);
+
+/*
+ * Host arithmetic. Rank that takes sequence `seq`'s token (its query, and its K/V in that
+ * rank's cache) at decode iteration `decode_iter`: the batch is dealt round-robin and the deal
+ * moves on by one rank per iteration (Section 3.6), so every rank's cache grows at the same
+ * rate. Returns the rank, or CP_ERR_SHAPE for n_ranks < 1 or a negative argument.
+ */
+int32_t cp_decode_owner(int32_t seq, int32_t decode_iter, int32_t n_ranks);
+
+/*
  * Measurement support (not a step of the paper's method): sustained rate of the matrix
  * pipe. Launches one workgroup of 8 wavefronts per entry of `n_workgroups`, each issuing
  * iters * 16 independent v_mfma_f32_32x32x16_bf16 on the operands found in

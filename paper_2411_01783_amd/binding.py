@@ -26,7 +26,8 @@ EXPORTS = [
     "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_partial_accumulate",
     "cp_attn_decode",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
-    "cp_ring_workspace_bytes", "cp_select_order", "cp_probe_mfma_rate", "cp_strerror",
+    "cp_ring_workspace_bytes", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
+    "cp_decode_owner", "cp_probe_mfma_rate", "cp_strerror",
     "cp_version",
 ]
 CP_PROBE_OPERAND_BYTES = 65536
@@ -116,6 +117,12 @@ def load() -> ctypes.CDLL:
     lib.cp_attn_partial_accumulate.restype = ctypes.c_int
     lib.cp_attn_partial_accumulate.argtypes = [ctypes.POINTER(cp_shape)] + [_vp] * 8 + [_i32] + \
         [_vp] * 2 + [ctypes.c_size_t, _vp]
+    lib.cp_kv_cache_reset.restype = ctypes.c_int
+    lib.cp_kv_cache_reset.argtypes = [ctypes.POINTER(cp_shape)] + [_vp] * 6
+    lib.cp_kv_append.restype = ctypes.c_int
+    lib.cp_kv_append.argtypes = [ctypes.POINTER(cp_shape)] + [_vp] * 11
+    lib.cp_decode_owner.restype = _i32
+    lib.cp_decode_owner.argtypes = [_i32, _i32, _i32]
     lib.cp_probe_mfma_rate.restype = ctypes.c_int
     lib.cp_probe_mfma_rate.argtypes = [_vp, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
     _lib = lib
@@ -288,6 +295,55 @@ def cp_attn_decode(q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid,
                               dtype_code(out.dtype), wp, wn, _stream(stream)),
            "cp_attn_decode")
     return out, lse
+
+
+class KVCache:
+    """Device buffers of one rank's persistent KV cache (see cp_kv_append in cp_attn.h):
+    a holder for the tensors, nothing else. `capacity[b]` slots per sequence."""
+
+    def __init__(self, capacity: Sequence[int], n_kv_heads: int, head_dim: int,
+                 dtype: torch.dtype = torch.bfloat16, device="cuda", stream=None):
+        cu = np.concatenate([[0], np.cumsum(np.asarray(capacity, dtype=np.int64))])
+        self.batch = len(capacity)
+        self.slots = int(cu[-1])
+        self.cu_host = cu.astype(np.int32)
+        self.cu = torch.as_tensor(self.cu_host).to(device)
+        self.k = torch.empty((self.slots, n_kv_heads, head_dim), dtype=dtype, device=device)
+        self.v = torch.empty_like(self.k)
+        self.kv_pos = torch.empty((self.slots,), dtype=torch.int32, device=device)
+        self.used = torch.empty((self.batch,), dtype=torch.int32, device=device)
+        self.dropped = torch.empty((1,), dtype=torch.int32, device=device)
+        shape = make_shape(dtype_code(dtype), head_dim, n_kv_heads, n_kv_heads, 0, self.slots,
+                           self.batch)
+        _check(load().cp_kv_cache_reset(ctypes.byref(shape), _ptr(self.k), _ptr(self.v),
+                                        _ptr(self.kv_pos), _ptr(self.used), _ptr(self.dropped),
+                                        _stream(stream)), "cp_kv_cache_reset")
+
+    def segment(self, b: int):
+        """(k, v, kv_pos) views of sequence b's slot range, unused slots included."""
+        lo, hi = int(self.cu_host[b]), int(self.cu_host[b + 1])
+        return self.k[lo:hi], self.v[lo:hi], self.kv_pos[lo:hi]
+
+
+def cp_kv_append(cache: KVCache, k_new: torch.Tensor, v_new: torch.Tensor,
+                 pos_new: torch.Tensor, cu_seqlens_new: torch.Tensor, stream=None) -> None:
+    """Append rows [cu_new[b], cu_new[b+1]) of k_new / v_new to sequence b of the cache."""
+    n_new, nkv, d = k_new.shape
+    shape = make_shape(dtype_code(k_new.dtype), d, nkv, nkv, n_new, cache.slots, cache.batch)
+    if k_new.dtype != cache.k.dtype or tuple(cache.k.shape[1:]) != (nkv, d):
+        raise ValueError("new K/V rows do not match the cache's row shape or dtype")
+    if cu_seqlens_new.numel() != cache.batch + 1 or pos_new.numel() != n_new:
+        raise ValueError("cu_seqlens_new / pos_new sizes do not match")
+    _check(load().cp_kv_append(ctypes.byref(shape), _ptr(k_new), _ptr(v_new), _ptr(pos_new),
+                               _ptr(cu_seqlens_new), _ptr(cache.k), _ptr(cache.v),
+                               _ptr(cache.kv_pos), _ptr(cache.cu), _ptr(cache.used),
+                               _ptr(cache.dropped), _stream(stream)), "cp_kv_append")
+
+
+def cp_decode_owner(seq: int, decode_iter: int, n_ranks: int) -> int:
+    r = int(load().cp_decode_owner(seq, decode_iter, n_ranks))
+    _check(min(r, 0), "cp_decode_owner")
+    return r
 
 
 def cp_attn_merge(outs: Sequence[torch.Tensor], lses: Sequence[torch.Tensor],

@@ -57,6 +57,44 @@ def test_probe_rejects_bad_arguments_before_any_launch(lib):
     assert lib.cp_probe_mfma_rate(one, 1, 0, one, ctypes.byref(flop), None) == -2
 
 
+def test_kv_cache_calls_validate_before_launching(lib):
+    one = ctypes.c_void_p(256)    # never dereferenced: every call below fails validation first
+    odd = ctypes.c_void_p(264)    # not 16-byte aligned
+    def reset(shape, k_cache=one, used=one):
+        return lib.cp_kv_cache_reset(ctypes.byref(shape), k_cache, one, one, used, None, None)
+    assert reset(B.make_shape(B.CP_BF16, 128, 1, 1, 0, -1, batch=2)) == -2
+    assert reset(B.make_shape(B.CP_BF16, 128, 1, 1, 0, 2 ** 31, batch=2)) == -2
+    assert reset(B.make_shape(B.CP_BF16, 128, 1, 1, 0, 64, batch=0)) == -2
+    assert reset(B.make_shape(B.CP_BF16, 12, 1, 1, 0, 64, batch=2)) == -3
+    assert reset(B.make_shape(B.CP_BF16, 128, 1, 1, 0, 64, batch=2), k_cache=None) == -1
+    assert reset(B.make_shape(B.CP_BF16, 128, 1, 1, 0, 64, batch=2), used=None) == -1
+    assert reset(B.make_shape(B.CP_BF16, 128, 1, 1, 0, 64, batch=2), k_cache=odd) == -6
+
+    def call(shape, k_new=one, cu_new=one, used=one, k_cache=one):
+        return lib.cp_kv_append(ctypes.byref(shape), k_new, one, one, cu_new, k_cache, one, one,
+                                one, used, None, None)
+    good = B.make_shape(B.CP_BF16, 128, 1, 1, 4, 64, batch=2)
+    assert call(good, k_new=None) == -1
+    assert call(good, cu_new=None) == -1
+    assert call(good, used=None) == -1
+    assert call(good, k_cache=odd) == -6
+    assert call(B.make_shape(7, 128, 1, 1, 4, 64, batch=2)) == -3
+    assert call(B.make_shape(B.CP_BF16, 100, 1, 1, 4, 64, batch=2)) == -3
+    assert call(B.make_shape(B.CP_BF16, 128, 1, 1, 4, 64, batch=0)) == -2
+    assert call(B.make_shape(B.CP_BF16, 128, 1, 1, -4, 64, batch=2)) == -2
+    # nothing to append: accepted without touching any buffer
+    assert call(B.make_shape(B.CP_BF16, 128, 1, 1, 0, 64, batch=2), k_new=None) == 0
+
+
+def test_decode_owner_matches_oracle(lib, oracle):
+    for n in (1, 3, 16):
+        for b in range(7):
+            for t in range(5):
+                assert lib.cp_decode_owner(b, t, n) == oracle.decode_owner(b, t, n)
+    assert lib.cp_decode_owner(0, 0, 0) == -2
+    assert lib.cp_decode_owner(-1, 0, 4) == -2
+
+
 def test_version_and_strerror(lib):
     assert B.cp_version() >= 100
     assert B.strerror(0) == "ok"
