@@ -238,26 +238,44 @@ def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False):
 # ---------------------------------------------------------------------------
 
 def bench_kv_append(reps: int = 20):
+    """`reps` appends recorded in one HIP graph and replayed (issued call by call from Python
+    they would be bound by the interpreter, not by the GPU)."""
+    def graph_time(fn):
+        for _ in range(3):
+            fn()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            side.synchronize()
+            g.capture_begin(capture_error_mode="relaxed")
+            for _ in range(reps):
+                fn()
+            g.capture_end()
+        torch.cuda.synchronize()
+        return time_steps(g.replay, 2, 1) / reps     # 3 replays + 3 eager calls in all
+
     w = W.WORKLOADS["prefill_128k"]
     rows = w.t_new // w.n_ranks                      # 8192 tokens of one sequence per rank
     k_new = W.normal(71, (rows, w.n_kv_heads, w.head_dim), w.dtype, "cuda")
     v_new = W.normal(72, (rows, w.n_kv_heads, w.head_dim), w.dtype, "cuda")
     pos = _i32(B.cp_shard_positions(w.t_new, w.n_ranks, 0))
     cu_new = _i32([0, rows])
-    cache = B.KVCache([rows * (reps + 4)], w.n_kv_heads, w.head_dim)
-    sec = time_steps(lambda: B.cp_kv_append(cache, k_new, v_new, pos, cu_new), reps, 3)
+    cache = B.KVCache([rows * (3 * reps + 4)], w.n_kv_heads, w.head_dim)
+    sec = graph_time(lambda: B.cp_kv_append(cache, k_new, v_new, pos, cu_new))
     moved = 2 * (2 * k_new.numel() * 2) + 2 * rows * 4          # K, V read + written; positions
-    res = {"prefill_rows": rows, "prefill_us": sec * 1e6, "prefill_gbs": moved / sec / 1e9}
+    res = {"prefill_rows": rows, "prefill_us": sec * 1e6, "prefill_gbs": moved / sec / 1e9,
+           "dropped": int(cache.dropped.item())}
     # decode step: the owner of 2 of 32 sequences appends one token each
     d = W.WORKLOADS["decode_b32"]
-    cache = B.KVCache([reps + 8] * d.batch, d.n_kv_heads, d.head_dim)
+    cache = B.KVCache([3 * reps + 4] * d.batch, d.n_kv_heads, d.head_dim)
     counts = np.zeros(d.batch, dtype=np.int64)
     counts[[0, d.n_ranks]] = 1
     cu_new = _i32(np.concatenate([[0], np.cumsum(counts)]))
-    sec = time_steps(lambda: B.cp_kv_append(cache, k_new[:2], v_new[:2], pos[:2], cu_new), reps, 3)
+    k2, v2, p2 = k_new[:2].contiguous(), v_new[:2].contiguous(), pos[:2].contiguous()
+    sec = graph_time(lambda: B.cp_kv_append(cache, k2, v2, p2, cu_new))
     res["decode_step_us"] = sec * 1e6
-    torch.cuda.synchronize()
-    res["dropped"] = int(cache.dropped.item())
+    res["dropped"] += int(cache.dropped.item())
     return {k: (round(v, 3) if isinstance(v, float) else v) for k, v in res.items()}
 
 

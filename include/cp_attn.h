@@ -253,7 +253,23 @@ typedef struct {
    * driver call; no device memory is allocated.
    */
   void* aux_stream;
+  /*
+   * 0: partial O and LSE in the two buffers described above. 1: partial_lse is not used and
+   * partial_out holds one message per slot, cp_ring_message_bytes(desc) apart: the slot's O
+   * (max_n_q * n_q_heads * head_dim elements of part_dtype) directly followed by its LSE
+   * (max_n_q * n_q_heads floats), padded to a multiple of 256 bytes. This is the unit the
+   * All2All of Algorithms 3 and 4 moves (Appendix C counts it as (D + 1) T e bytes): with
+   * keep_partials in the pass-Q drivers, the N messages that rank s receives, from holders
+   * k = 0..N-1 in order, are slots s * n_ranks + k, one contiguous range, and each is
+   * written in place by the attention kernel and read in place by the merge: no pack,
+   * permute or unpack pass.
+   */
+  int32_t message_layout;
 } cp_ring_desc;
+
+/* Bytes of one message of message_layout 1 (see cp_ring_desc); 0 for an invalid descriptor.
+ * Host arithmetic; reads n_ranks, n_q, n_q_heads, head_dim, part_dtype. */
+size_t cp_ring_message_bytes(const cp_ring_desc* desc);
 
 /*
  * Ring pass-KV, Algorithm 2, for every virtual rank k: for j = 0..N-1,
@@ -327,8 +343,10 @@ int cp_select_order(const cp_select_params* params, int64_t t_new, int64_t p_cac
  *   k_cache, v_cache  [slots, n_kv_heads, head_dim] in shape->dtype, 16-byte aligned
  *   kv_pos_cache      int32 [slots]
  *   cu_seqlens_kv     int32 [batch+1]: sequence b owns slots [cu[b], cu[b+1]), its capacity
- *   seq_used          int32 [batch]: tokens held per sequence; they fill the front of the
- *                     sequence's slot range in arrival order
+ *   seq_used          int32 [batch+1]: tokens held per sequence (they fill the front of the
+ *                     sequence's slot range in arrival order), followed by one word the
+ *                     library uses as a ticket counter inside cp_kv_append; it is zero
+ *                     between calls
  * A slot that holds no token carries CP_POS_PAD_KV in kv_pos_cache, which no query position
  * reaches: cp_attn_decode, cp_attn_partial and the ring drivers take the cache (or one
  * sequence's slot range of it) as it is, with cu_seqlens_kv as the sequence boundaries.
@@ -354,8 +372,8 @@ int cp_kv_cache_reset(const cp_shape* shape, void* k_cache, void* v_cache,
  *   seq_used        (device) read, then advanced by the number of tokens taken
  *   dropped         (device) int32 or NULL: incremented by the number of tokens that did not
  *                   fit their sequence's capacity (those are not stored)
- * Two launches on `stream` (copy, then the update of seq_used); calls on one cache must be
- * ordered by the caller (same stream or events).
+ * One launch on `stream` for small calls (up to 1024 tokens of a 256-byte row), two for
+ * larger ones; calls on one cache must be ordered by the caller (same stream or events).
  * Errors: CP_ERR_NULL, CP_ERR_SHAPE, CP_ERR_UNSUPPORTED (dtype, head_dim), CP_ERR_ALIGN.
  */
 int cp_kv_append(const cp_shape* shape, const void* k_new, const void* v_new,

@@ -26,7 +26,7 @@ EXPORTS = [
     "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_partial_accumulate",
     "cp_attn_decode",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
-    "cp_ring_workspace_bytes", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
+    "cp_ring_workspace_bytes", "cp_ring_message_bytes", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
     "cp_decode_owner", "cp_probe_mfma_rate", "cp_strerror",
     "cp_version",
 ]
@@ -55,7 +55,7 @@ class cp_ring_desc(ctypes.Structure):
                 ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t),
                 ("batch", _i32),
                 ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp)),
-                ("aux_stream", _vp)]
+                ("aux_stream", _vp), ("message_layout", _i32)]
 
 
 class cp_select_params(ctypes.Structure):
@@ -111,6 +111,8 @@ def load() -> ctypes.CDLL:
         fn.argtypes = [ctypes.POINTER(cp_ring_desc), _vp]
     lib.cp_ring_workspace_bytes.restype = ctypes.c_size_t
     lib.cp_ring_workspace_bytes.argtypes = [ctypes.POINTER(cp_ring_desc), _i32]
+    lib.cp_ring_message_bytes.restype = ctypes.c_size_t
+    lib.cp_ring_message_bytes.argtypes = [ctypes.POINTER(cp_ring_desc)]
     lib.cp_select_order.restype = ctypes.c_int
     lib.cp_select_order.argtypes = [ctypes.POINTER(cp_select_params), _i64, _i64, _i32,
                                     ctypes.POINTER(_i32)]
@@ -311,7 +313,7 @@ class KVCache:
         self.k = torch.empty((self.slots, n_kv_heads, head_dim), dtype=dtype, device=device)
         self.v = torch.empty_like(self.k)
         self.kv_pos = torch.empty((self.slots,), dtype=torch.int32, device=device)
-        self.used = torch.empty((self.batch,), dtype=torch.int32, device=device)
+        self.used = torch.empty((self.batch + 1,), dtype=torch.int32, device=device)  # + ticket word
         self.dropped = torch.empty((1,), dtype=torch.int32, device=device)
         shape = make_shape(dtype_code(dtype), head_dim, n_kv_heads, n_kv_heads, 0, self.slots,
                            self.batch)
@@ -376,7 +378,7 @@ class Ring:
                  keep_partials: bool = False, softmax_scale: float = 0.0,
                  cu_seqlens_kv: Optional[List[torch.Tensor]] = None,
                  bid: Optional[List[torch.Tensor]] = None, aux_stream=None,
-                 fused_merge: bool = False):
+                 fused_merge: bool = False, message_layout: bool = False):
         n = len(q)
         self.n = n
         self.decode = cu_seqlens_kv is not None
@@ -392,8 +394,10 @@ class Ring:
         max_q = max(self.n_q) if self.n_q else 0
         slots = n * n if keep_partials else (1 if fused_merge else n)
         self.keep = keep_partials
-        self.partial_out = torch.empty((slots, max_q, nh, d), dtype=part_dtype, device=dev)
-        self.partial_lse = torch.empty((slots, max_q, nh), dtype=torch.float32, device=dev)
+        self.messages = None
+        if not message_layout:
+            self.partial_out = torch.empty((slots, max_q, nh, d), dtype=part_dtype, device=dev)
+            self.partial_lse = torch.empty((slots, max_q, nh), dtype=torch.float32, device=dev)
 
         def parr(ts):
             return (_vp * n)(*[(_ptr(t) if t is not None and t.numel() > 0 else None) for t in ts])
@@ -408,7 +412,19 @@ class Ring:
         dsc.out_dtype, dsc.part_dtype = dtype_code(odt), dtype_code(part_dtype)
         for name, arr in self._arrs.items():
             setattr(dsc, name, ctypes.cast(arr, type(getattr(dsc, name))))
-        dsc.partial_out, dsc.partial_lse = _ptr(self.partial_out), _ptr(self.partial_lse)
+        if message_layout:
+            # one buffer of messages (O of the slot, then its LSE), see cp_ring_desc
+            dsc.message_layout = 1
+            self.message_bytes = int(load().cp_ring_message_bytes(ctypes.byref(dsc)))
+            self.messages = torch.empty((slots, self.message_bytes), dtype=torch.uint8,
+                                        device=dev)
+            o_bytes = max_q * nh * d * torch.empty(0, dtype=part_dtype).element_size()
+            self.partial_out = self.messages[:, :o_bytes].view(part_dtype).view(slots, max_q, nh, d)
+            self.partial_lse = self.messages[:, o_bytes:o_bytes + max_q * nh * 4] \
+                .view(torch.float32).view(slots, max_q, nh)
+            dsc.partial_out, dsc.partial_lse = _ptr(self.messages), None
+        else:
+            dsc.partial_out, dsc.partial_lse = _ptr(self.partial_out), _ptr(self.partial_lse)
         dsc.keep_partials = 1 if keep_partials else 0
         dsc.fused_merge = 1 if fused_merge else 0
         if self.decode:

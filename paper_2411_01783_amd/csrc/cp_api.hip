@@ -221,12 +221,14 @@ static int check_ring(const cp_ring_desc* d, bool decode) {
   if (d == nullptr) return CP_ERR_NULL;
   if (d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS) return CP_ERR_SHAPE;
   if (d->fused_merge != 0 && d->fused_merge != 1) return CP_ERR_SHAPE;
+  if (d->message_layout != 0 && d->message_layout != 1) return CP_ERR_SHAPE;
   if (d->fused_merge && (decode || d->keep_partials || d->part_dtype != CP_FP32))
     return CP_ERR_UNSUPPORTED;
   if (d->n_q == nullptr || d->n_kv == nullptr || d->q == nullptr || d->k == nullptr ||
       d->v == nullptr || d->q_pos == nullptr || d->kv_pos == nullptr || d->out == nullptr)
     return CP_ERR_NULL;
-  if (d->partial_out == nullptr || d->partial_lse == nullptr) return CP_ERR_NULL;
+  if (d->partial_out == nullptr || (d->partial_lse == nullptr && !d->message_layout))
+    return CP_ERR_NULL;
   if (d->part_dtype != CP_BF16 && d->part_dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
   if (d->out_dtype != CP_BF16 && d->out_dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
   if (!aligned16(d->partial_out)) return CP_ERR_ALIGN;
@@ -287,21 +289,36 @@ extern "C" size_t cp_ring_workspace_bytes(const cp_ring_desc* d, int32_t decode)
 
 namespace {
 
+// Where the partial (O, LSE) of a slot live. Two buffers, or (message_layout) one buffer of
+// messages, each the slot's O followed by its LSE: what the All2All of Algorithms 3 and 4
+// moves as one piece, written in place by the attention kernel and read in place by the merge.
 struct RingSlots {
   int64_t max_q = 0;
   size_t out_slot_bytes = 0;
   size_t lse_slot_elems = 0;
+  size_t out_stride = 0;   // bytes between the O of consecutive slots
+  bool messages = false;
   char* out_base = nullptr;
   float* lse_base = nullptr;
-  void* out(int64_t slot) const { return out_base + slot * out_slot_bytes; }
-  float* lse(int64_t slot) const { return lse_base + slot * lse_slot_elems; }
+  void* out(int64_t slot) const { return out_base + slot * out_stride; }
+  float* lse(int64_t slot) const {
+    return messages ? (float*)(out_base + slot * out_stride + out_slot_bytes)
+                    : lse_base + slot * lse_slot_elems;
+  }
 };
+
+size_t ring_message_bytes(size_t out_slot_bytes, size_t lse_slot_elems) {
+  return (out_slot_bytes + lse_slot_elems * sizeof(float) + 255) / 256 * 256;
+}
 
 RingSlots make_slots(const cp_ring_desc* d) {
   RingSlots r;
   for (int i = 0; i < d->n_ranks; ++i) r.max_q = std::max<int64_t>(r.max_q, d->n_q[i]);
   r.lse_slot_elems = (size_t)r.max_q * d->n_q_heads;
   r.out_slot_bytes = r.lse_slot_elems * d->head_dim * elem_size(d->part_dtype);
+  r.messages = d->message_layout != 0;
+  r.out_stride = r.messages ? ring_message_bytes(r.out_slot_bytes, r.lse_slot_elems)
+                            : r.out_slot_bytes;
   r.out_base = (char*)d->partial_out;
   r.lse_base = d->partial_lse;
   return r;
@@ -444,6 +461,16 @@ int ring_merge(const cp_ring_desc* d, const RingSlots& slots, int a, int64_t fir
 }  // namespace
 
 extern "C" {
+
+size_t cp_ring_message_bytes(const cp_ring_desc* d) {
+  if (d == nullptr || d->n_q == nullptr || d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS) return 0;
+  if (d->part_dtype != CP_BF16 && d->part_dtype != CP_FP32) return 0;
+  if (d->n_q_heads < 1 || d->head_dim < 1) return 0;
+  for (int i = 0; i < d->n_ranks; ++i)
+    if (d->n_q[i] < 0) return 0;
+  const RingSlots r = make_slots(d);
+  return ring_message_bytes(r.out_slot_bytes, r.lse_slot_elems);
+}
 
 int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
   int rc = check_ring(d, false);

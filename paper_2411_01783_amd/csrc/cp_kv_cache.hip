@@ -30,6 +30,8 @@ struct AppendParams {
   int64_t slots;
 };
 
+constexpr int64_t kTicketMaxBlocks = 64;  // above: two launches, see kv_append_kernel
+
 // Sequence that new token i belongs to: the b with cu_new[b] <= i < cu_new[b+1].
 __device__ __forceinline__ int find_sequence(const int32_t* cu_new, int batch, int64_t i) {
   int lo = 0, hi = batch;  // invariant: cu_new[lo] <= i < cu_new[hi]
@@ -40,34 +42,58 @@ __device__ __forceinline__ int find_sequence(const int32_t* cu_new, int batch, i
   return lo;
 }
 
+// seq_used[] may only change once every workgroup has read it.
+// TICKET (calls of a few workgroups, e.g. a decode step's tokens): one launch. Every workgroup
+// takes a ticket (the word after the last sequence's count) after its reads; the one that
+// draws the last ticket advances the counts, counts what did not fit and zeroes the ticket
+// word. Tickets are atomics on one address, about 10 ns each across XCDs, so large calls use
+// a second launch (kv_append_commit_kernel) instead.
+__device__ __forceinline__ void commit_counts(const AppendParams& p) {
+  for (int b = threadIdx.x; b < p.batch; b += blockDim.x) {
+    const int32_t n_new = p.cu_new[b + 1] - p.cu_new[b];
+    const int32_t room = p.cu_kv[b + 1] - p.cu_kv[b] - p.used[b];
+    int32_t taken = n_new < room ? n_new : room;
+    if (taken < 0) taken = 0;
+    p.used[b] += taken;
+    if (p.dropped != nullptr && n_new > taken) atomicAdd(p.dropped, n_new - taken);
+  }
+}
+
+template <bool TICKET>
 __global__ __launch_bounds__(256) void kv_append_kernel(AppendParams p) {
   const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t i = t / p.chunks_per_token;
-  if (i >= p.n_new) return;
-  const int c = (int)(t - i * p.chunks_per_token);
-  const int b = find_sequence(p.cu_new, p.batch, i);
-  const int64_t first = p.cu_kv[b], used = p.used[b], off = i - p.cu_new[b];
-  const int64_t slot = first + used + off;
-  // Over capacity: dropped (the second kernel counts it). The remaining conditions hold for
-  // consistent bookkeeping arrays; they keep inconsistent ones from writing outside the cache.
-  if (slot >= p.cu_kv[b + 1] || slot >= p.slots || first < 0 || used < 0 || off < 0) return;
-  const int64_t src = i * p.chunks_per_token + c;
-  const int64_t dst = slot * p.chunks_per_token + c;
-  p.k_cache[dst] = p.k_new[src];
-  p.v_cache[dst] = p.v_new[src];
-  if (c == 0) p.pos_cache[slot] = p.pos_new[i];
+  if (i < p.n_new) {
+    const int c = (int)(t - i * p.chunks_per_token);
+    const int b = find_sequence(p.cu_new, p.batch, i);
+    const int64_t first = p.cu_kv[b], used = p.used[b], off = i - p.cu_new[b];
+    const int64_t slot = first + used + off;
+    // Over capacity: dropped (counted at the commit). The remaining conditions hold for
+    // consistent bookkeeping arrays; they keep inconsistent ones from writing outside the cache.
+    if (slot < p.cu_kv[b + 1] && slot < p.slots && first >= 0 && used >= 0 && off >= 0) {
+      const int64_t src = i * p.chunks_per_token + c;
+      const int64_t dst = slot * p.chunks_per_token + c;
+      p.k_cache[dst] = p.k_new[src];
+      p.v_cache[dst] = p.v_new[src];
+      if (c == 0) p.pos_cache[slot] = p.pos_new[i];
+    }
+  }
+  if (!TICKET) return;
+  __shared__ int last;
+  __syncthreads();  // every thread of the workgroup has read its count
+  // No fence: what must come first are the workgroups' *reads* of the counts, and those have
+  // returned their values before the barrier above. (A release fence here would write back
+  // the L2 of the workgroup's XCD, K/V rows included, once per workgroup.)
+  if (threadIdx.x == 0) last = atomicAdd(p.used + p.batch, 1) == (int)gridDim.x - 1;
+  __syncthreads();
+  if (!last) return;
+  commit_counts(p);
+  if (threadIdx.x == 0) p.used[p.batch] = 0;
 }
 
-// Runs after kv_append_kernel on the same stream: only now may used[] change.
+// Second launch of a large call, after kv_append_kernel<false> on the same stream.
 __global__ __launch_bounds__(256) void kv_append_commit_kernel(AppendParams p) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= p.batch) return;
-  const int32_t n_new = p.cu_new[b + 1] - p.cu_new[b];
-  const int32_t room = p.cu_kv[b + 1] - p.cu_kv[b] - p.used[b];
-  int32_t taken = n_new < room ? n_new : (room > 0 ? room : 0);
-  if (taken < 0) taken = 0;
-  p.used[b] += taken;
-  if (p.dropped != nullptr && n_new > taken) atomicAdd(p.dropped, n_new - taken);
+  commit_counts(p);
 }
 
 // Unused slots must not hold NaN or Inf patterns: a masked key still enters the P V product
@@ -84,7 +110,7 @@ __global__ __launch_bounds__(256) void kv_cache_reset_kernel(uint4* k_cache, uin
     v_cache[c] = zero;
   }
   for (int64_t i = t; i < slots; i += stride) pos_cache[i] = CP_POS_PAD_KV;
-  for (int64_t i = t; i < batch; i += stride) used[i] = 0;
+  for (int64_t i = t; i <= batch; i += stride) used[i] = 0;  // counts and the ticket word
   if (t == 0 && dropped != nullptr) *dropped = 0;
 }
 
@@ -149,10 +175,13 @@ int cp_kv_append(const cp_shape* shape, const void* k_new, const void* v_new,
   const int64_t blocks = (threads + 255) / 256;
   if (blocks > INT32_MAX) return CP_ERR_SHAPE;
   hipStream_t st = (hipStream_t)stream;
-  hipLaunchKernelGGL(cp::kv_append_kernel, dim3((unsigned)blocks), dim3(256), 0, st, p);
+  if (blocks <= cp::kTicketMaxBlocks) {
+    hipLaunchKernelGGL(cp::kv_append_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, p);
+    return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
+  }
+  hipLaunchKernelGGL(cp::kv_append_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, p);
   if (hipGetLastError() != hipSuccess) return CP_ERR_LAUNCH;
-  hipLaunchKernelGGL(cp::kv_append_commit_kernel, dim3((unsigned)((s.batch + 255) / 256)),
-                     dim3(256), 0, st, p);
+  hipLaunchKernelGGL(cp::kv_append_commit_kernel, dim3(1), dim3(256), 0, st, p);
   return hipGetLastError() == hipSuccess ? CP_OK : CP_ERR_LAUNCH;
 }
 

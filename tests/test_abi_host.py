@@ -225,6 +225,28 @@ def test_ring_descriptor_validation(lib):
     assert lib.cp_ring_passq(ctypes.byref(d), None) == -1
     assert lib.cp_ring_passq_decode(ctypes.byref(d), None) == -1
     assert lib.cp_ring_workspace_bytes(ctypes.byref(d), 0) == 0
+    d.message_layout = 2
+    assert lib.cp_ring_passkv(ctypes.byref(d), None) == -2
+    d.message_layout = 0
+
+
+def test_ring_message_bytes(lib):
+    d = B.cp_ring_desc()
+    assert lib.cp_ring_message_bytes(None) == 0
+    assert lib.cp_ring_message_bytes(ctypes.byref(d)) == 0      # no ranks
+    n_q = (ctypes.c_int64 * 3)(5, 8192, 100)
+    d.n_ranks, d.n_q_heads, d.head_dim, d.part_dtype = 3, 16, 128, B.CP_BF16
+    d.n_q = ctypes.cast(n_q, type(d.n_q))
+    # O of the largest shard (D elements a row) and its LSE (one float a row), to 256 bytes:
+    # Appendix C's (D + 1) per row with the LSE kept in fp32
+    rows = 8192 * 16
+    assert lib.cp_ring_message_bytes(ctypes.byref(d)) == rows * 128 * 2 + rows * 4
+    d.part_dtype = B.CP_FP32
+    assert lib.cp_ring_message_bytes(ctypes.byref(d)) == rows * (128 + 1) * 4
+    n_q[1] = 7
+    assert lib.cp_ring_message_bytes(ctypes.byref(d)) == -(-(100 * 16 * 129 * 4) // 256) * 256
+    d.part_dtype = 9
+    assert lib.cp_ring_message_bytes(ctypes.byref(d)) == 0
 
 
 def test_product_does_not_import_the_oracle():

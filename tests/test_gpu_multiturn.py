@@ -24,7 +24,9 @@ def assert_cache_equals(cache: B.KVCache, ref, what=""):
     torch.cuda.synchronize()
     k_ref, v_ref, pos_ref, cu_ref = ref.packed()
     np.testing.assert_array_equal(cache.cu.cpu().numpy(), cu_ref, err_msg=what)
-    np.testing.assert_array_equal(cache.used.cpu().numpy(), ref.used(), err_msg=what)
+    used = cache.used.cpu().numpy()
+    np.testing.assert_array_equal(used[:-1], ref.used(), err_msg=what)
+    assert used[-1] == 0, what + ": the ticket word must be zero between calls"
     np.testing.assert_array_equal(cache.kv_pos.cpu().numpy(), pos_ref, err_msg=what)
     assert int(cache.dropped.item()) == ref.dropped, what
     np.testing.assert_array_equal(W.to_f64(cache.k.cpu()), k_ref, err_msg=what)

@@ -512,3 +512,55 @@ def test_ring_passq_partial_prefill(oracle, partition):
     torch.cuda.synchronize()
     for r, (qp, _) in enumerate(sh):
         check(out2[r], lse2[r], ref_o[qp - p_cached], ref_l[qp - p_cached])
+
+
+@pytest.mark.parametrize("part", ["fp32", "bf16"])
+def test_ring_passq_all2all_messages(oracle, part):
+    """Partials written in place as All2All messages (O of the slot, then its LSE): the raw
+    buffer, decoded here from the documented layout, holds the oracle's per-(source, holder)
+    partials, the N messages a rank receives are one contiguous range, and the merged
+    results are those of the two-buffer layout."""
+    n, p_cached, t_new, nh, d = 4, 1000, 333, 16, 128
+    q, q64 = randn(121, (t_new, nh, d))
+    k, k64 = randn(122, (p_cached + t_new, 1, d))
+    v, v64 = randn(123, (p_cached + t_new, 1, d))
+    sh = oracle.shard_partial_prefill(p_cached, t_new, n)
+    qs64 = [q64[qp - p_cached] for qp, _ in sh]
+    ref_o, ref_l, part_o, part_l = oracle.ring_passq(
+        qs64, [k64[kp] for _, kp in sh], [v64[kp] for _, kp in sh],
+        [qp for qp, _ in sh], [kp for _, kp in sh])
+    pdt = torch.float32 if part == "fp32" else torch.bfloat16
+    args = ([dev(q[qp - p_cached]) for qp, _ in sh], [dev(k[kp]) for _, kp in sh],
+            [dev(v[kp]) for _, kp in sh], [i32(qp) for qp, _ in sh], [i32(kp) for _, kp in sh])
+    ring = B.Ring(*args, out_dtype=torch.float32, part_dtype=pdt, keep_partials=True,
+                  message_layout=True)
+    out, lse = B.cp_ring_passq(ring)
+    torch.cuda.synchronize()
+    for s in range(n):
+        check(out[s], lse[s], ref_o[s], ref_l[s], what="merged, source rank %d" % s)
+    plain = B.Ring(*args, out_dtype=torch.float32, part_dtype=pdt, keep_partials=True)
+    out_p, lse_p = B.cp_ring_passq(plain)
+    torch.cuda.synchronize()
+    for s in range(n):
+        assert torch.equal(out[s], out_p[s]) and torch.equal(lse[s], lse_p[s])
+    # the raw messages
+    raw = ring.messages.cpu()
+    max_q = max(len(qp) for qp, _ in sh)
+    e = 4 if part == "fp32" else 2
+    o_bytes, l_bytes = max_q * nh * d * e, max_q * nh * 4
+    assert ring.message_bytes % 256 == 0 and 0 <= ring.message_bytes - o_bytes - l_bytes < 256
+    assert raw.shape == (n * n, ring.message_bytes)
+    for s in range(n):          # receiver (source of the queries)
+        rows = len(sh[s][0])
+        for kk in range(n):     # sender (holder of the KV): message s*n + kk
+            msg = raw[s * n + kk]
+            o = msg[:o_bytes].view(pdt).view(max_q, nh, d)[:rows]
+            l = msg[o_bytes:o_bytes + l_bytes].view(torch.float32).view(max_q, nh)[:rows]
+            check(o, l, part_o[s][kk], part_l[s][kk], what="message %d <- %d" % (s, kk))
+    # without keep_partials the N reusable slots are messages too (pass-KV, pass-Q)
+    small = B.Ring(*args, out_dtype=torch.float32, part_dtype=pdt, message_layout=True)
+    for fn in (B.cp_ring_passq, B.cp_ring_passkv):
+        o2, l2 = fn(small)
+        torch.cuda.synchronize()
+        for s in range(n):
+            check(o2[s], l2[s], ref_o[s], ref_l[s], what="N-slot messages, rank %d" % s)
