@@ -355,6 +355,30 @@ def mfma_rate_probe(iters: int = 20000, reps: int = 3):
     return out
 
 
+def hbm_read_probe(nbytes: int, n_buffers: int = 16, reps: int = 5):
+    """What one launch that only reads `nbytes` once achieves (ramp and tail included), cycling
+    over `n_buffers` buffers as the decode measurement cycles over the ranks' KV (no reuse from
+    the 256 MB memory-side cache): the yardstick for the decode kernel."""
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    bufs = [torch.ones(nbytes // 4, dtype=torch.float32, device="cuda") for _ in range(n_buffers)]
+    out = {"bytes": nbytes, "us_by_wg_per_cu": {}}
+    best = None
+    for wg_per_cu in (1, 2, 3, 4):
+        n_wg = n_cu * wg_per_cu
+        sink = torch.empty(n_wg * 256, dtype=torch.int32, device="cuda")
+
+        def one_pass():
+            for b in bufs:
+                B.cp_probe_hbm_read(b, n_wg, sink)
+        sec = time_steps(one_pass, reps, 2) / n_buffers
+        out["us_by_wg_per_cu"][str(wg_per_cu)] = round(sec * 1e6, 2)
+        best = sec if best is None else min(best, sec)
+    out["best_us"] = round(best * 1e6, 2)
+    out["best_gbs"] = round(nbytes / best / 1e9, 1)
+    out["best_frac_hbm"] = round(nbytes / best / 1e9 / PEAK_HBM_GBS, 4)
+    return out
+
+
 def pmc_probe(ring):
     """The work the counter runs profile: a streaming kernel that reads and writes
     PROBE_COPY_BYTES (the scale reference), one pass-KV ring pass, one decode pass."""
@@ -462,6 +486,9 @@ def main():
         d = bench_decode(W.WORKLOADS["decode_b32"], graph=True)
         result["aux"]["decode"] = {k: (round(v, 4) if isinstance(v, float) else v)
                                    for k, v in d.items()}
+        torch.cuda.empty_cache()
+        result["aux"]["hbm_read_probe"] = hbm_read_probe(
+            int(d["kv_mb_per_rank"] * 1e6) // 4096 * 4096)
         torch.cuda.empty_cache()
         result["aux"]["partial_prefill"] = bench_partial_prefill(
             ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",

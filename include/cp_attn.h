@@ -404,6 +404,18 @@ int32_t cp_decode_owner(int32_t seq, int32_t decode_iter, int32_t n_ranks);
 int cp_probe_mfma_rate(const void* operands, int32_t iters, int32_t n_workgroups, void* sink,
                        double* flop_out, void* hip_stream);
 
+/*
+ * Measurement support (not a step of the paper's method): one launch of n_workgroups
+ * workgroups of 256 threads that reads `bytes` bytes (a multiple of 16) of `buffer` (device,
+ * 16-byte aligned) exactly once with non-temporal 16-byte loads and writes one word per
+ * thread to `sink` (device, n_workgroups * 256 words). Its duration is what a single launch
+ * that only streams that many bytes achieves on this part, launch ramp and tail included:
+ * the yardstick for the split-KV decode kernel beside the published HBM peak.
+ * Asynchronous on hip_stream. Errors: CP_ERR_NULL, CP_ERR_SHAPE, CP_ERR_ALIGN, CP_ERR_LAUNCH.
+ */
+int cp_probe_hbm_read(const void* buffer, size_t bytes, int32_t n_workgroups, void* sink,
+                      void* hip_stream);
+
 /* Static description of a cp_status. Never NULL. */
 const char* cp_strerror(int status);
 

@@ -27,7 +27,7 @@ EXPORTS = [
     "cp_attn_decode",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
     "cp_ring_workspace_bytes", "cp_ring_message_bytes", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
-    "cp_decode_owner", "cp_probe_mfma_rate", "cp_strerror",
+    "cp_decode_owner", "cp_probe_mfma_rate", "cp_probe_hbm_read", "cp_strerror",
     "cp_version",
 ]
 CP_PROBE_OPERAND_BYTES = 65536
@@ -125,6 +125,8 @@ def load() -> ctypes.CDLL:
     lib.cp_kv_append.argtypes = [ctypes.POINTER(cp_shape)] + [_vp] * 11
     lib.cp_decode_owner.restype = _i32
     lib.cp_decode_owner.argtypes = [_i32, _i32, _i32]
+    lib.cp_probe_hbm_read.restype = ctypes.c_int
+    lib.cp_probe_hbm_read.argtypes = [_vp, ctypes.c_size_t, _i32, _vp, _vp]
     lib.cp_probe_mfma_rate.restype = ctypes.c_int
     lib.cp_probe_mfma_rate.argtypes = [_vp, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
     _lib = lib
@@ -186,6 +188,17 @@ def cp_probe_mfma_rate(operands: torch.Tensor, iters: int, n_workgroups: int,
     _check(load().cp_probe_mfma_rate(_ptr(operands), int(iters), int(n_workgroups), _ptr(sink),
                                      ctypes.byref(flop), _stream(stream)), "cp_probe_mfma_rate")
     return flop.value
+
+
+def cp_probe_hbm_read(buffer: torch.Tensor, n_workgroups: int, sink: torch.Tensor,
+                      stream=None) -> int:
+    """One streaming read of the whole buffer; returns the bytes read."""
+    nbytes = buffer.numel() * buffer.element_size()
+    if sink.numel() * sink.element_size() < n_workgroups * 256 * 4:
+        raise ValueError("sink too small")
+    _check(load().cp_probe_hbm_read(_ptr(buffer), nbytes, n_workgroups, _ptr(sink),
+                                    _stream(stream)), "cp_probe_hbm_read")
+    return nbytes
 
 
 def cp_shard_positions(total: int, n_ranks: int, rank: int, offset: int = 0) -> np.ndarray:

@@ -34,6 +34,37 @@ __global__ __launch_bounds__(512) void mfma_rate_probe_kernel(const bf16x8_t* __
   sink[blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
+// What one launch that does nothing but read `n_chunks` 16-byte chunks once sustains: every
+// thread walks the buffer with a grid-wide stride, non-temporal loads, eight in flight, and
+// folds what it read into one word so that no load can be dropped.
+__global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4* __restrict__ in,
+                                                             int64_t n_chunks,
+                                                             uint32_t* __restrict__ sink) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t acc = 0;
+#ifndef CP_PROBE_DEPTH
+#define CP_PROBE_DEPTH 8
+#endif
+  constexpr int DEPTH = CP_PROBE_DEPTH;
+  for (; i + (DEPTH - 1) * stride < n_chunks; i += DEPTH * stride) {
+    uint4 t[DEPTH];
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) {
+      typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+      t[u] = __builtin_bit_cast(uint4,
+                                __builtin_nontemporal_load((const u32x4_t*)(in + i + u * stride)));
+    }
+#pragma unroll
+    for (int u = 0; u < DEPTH; ++u) acc ^= t[u].x ^ t[u].y ^ t[u].z ^ t[u].w;
+  }
+  for (; i < n_chunks; i += stride) {
+    const uint4 t = in[i];
+    acc ^= t.x ^ t.y ^ t.z ^ t.w;
+  }
+  sink[(int64_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
 }  // namespace
 }  // namespace cp
 
@@ -48,4 +79,15 @@ extern "C" int cp_probe_mfma_rate(const void* operands, int32_t iters, int32_t n
   // 8 wavefronts x 16 MFMAs per iteration, 2 * 32 * 32 * 16 operations each
   *flop_out = (double)n_workgroups * 8.0 * (double)iters * 16.0 * 32768.0;
   return CP_OK;
+}
+
+extern "C" int cp_probe_hbm_read(const void* buffer, size_t bytes, int32_t n_workgroups,
+                                 void* sink, void* hip_stream) {
+  if (buffer == nullptr || sink == nullptr) return CP_ERR_NULL;
+  if (n_workgroups < 1 || bytes < 16 || bytes % 16 != 0) return CP_ERR_SHAPE;
+  if (((uintptr_t)buffer & 15u) != 0) return CP_ERR_ALIGN;
+  hipLaunchKernelGGL(cp::hbm_read_probe_kernel, dim3(n_workgroups), dim3(256), 0,
+                     (hipStream_t)hip_stream, (const uint4*)buffer, (int64_t)(bytes / 16),
+                     (uint32_t*)sink);
+  return cp::check_launch();
 }

@@ -95,6 +95,16 @@ def test_decode_owner_matches_oracle(lib, oracle):
     assert lib.cp_decode_owner(-1, 0, 4) == -2
 
 
+def test_hbm_probe_rejects_bad_arguments_before_any_launch(lib):
+    one = ctypes.c_void_p(256)  # never dereferenced: every call below fails validation first
+    assert lib.cp_probe_hbm_read(None, ctypes.c_size_t(1024), 1, one, None) == -1
+    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(1024), 1, None, None) == -1
+    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(1000), 1, one, None) == -2
+    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(0), 1, one, None) == -2
+    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(1024), 0, one, None) == -2
+    assert lib.cp_probe_hbm_read(ctypes.c_void_p(260), ctypes.c_size_t(1024), 1, one, None) == -6
+
+
 def test_version_and_strerror(lib):
     assert B.cp_version() >= 100
     assert B.strerror(0) == "ok"

@@ -564,3 +564,20 @@ def test_ring_passq_all2all_messages(oracle, part):
         torch.cuda.synchronize()
         for s in range(n):
             check(o2[s], l2[s], ref_o[s], ref_l[s], what="N-slot messages, rank %d" % s)
+
+
+# ---------------------------------------------------------------------------
+# measurement support: the streaming-read probe reads every chunk exactly once
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n_words,n_wg", [(4, 1), (4 * 256 * 8 * 3 + 52, 3), (1 << 20, 64)])
+def test_hbm_read_probe_reads_every_chunk_once(n_words, n_wg):
+    rng = np.random.default_rng(5)
+    host = rng.integers(0, 2 ** 31 - 1, n_words, dtype=np.int32)
+    buf = torch.as_tensor(host).to("cuda")
+    sink = torch.zeros(n_wg * 256, dtype=torch.int32, device="cuda")
+    assert B.cp_probe_hbm_read(buf, n_wg, sink) == n_words * 4
+    torch.cuda.synchronize()
+    # the xor of what the threads folded is the xor of the buffer iff no chunk was skipped or
+    # read twice (random words: a chunk read twice cancels, a skipped one is missing)
+    assert np.bitwise_xor.reduce(sink.cpu().numpy()) == np.bitwise_xor.reduce(host)
