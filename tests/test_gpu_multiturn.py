@@ -137,3 +137,114 @@ def test_multi_turn_replay(oracle):
     for r in range(n):
         assert_cache_equals(caches[r], ref_caches[r], "rank %d cache after the last turn" % r)
         assert ref_caches[r].dropped == 0
+
+
+def test_decode_step_under_a_hip_graph(oracle):
+    """A decode step (append of the new tokens' K/V on their owners, then the pass-Q decode
+    ring) recorded once and replayed: every replay, with new queries and new K/V written into
+    the same input buffers and eager work in between, matches the eager result bit for bit and
+    the oracle within the bars; the caches grow by one token per sequence per replay."""
+    n, nh, d, n_seq, n_steps = 4, 16, 128, 8, 4
+    first = [300, 31, 1200, 64, 513, 5, 777, 128]
+    cap = [-(-L // n) + n_steps + 2 for L in first]
+    total = [L + n_steps for L in first]
+    qs = [W.normal(700 + b, (total[b], nh, d)) for b in range(n_seq)]
+    ks = [W.normal(720 + b, (total[b], 1, d)) for b in range(n_seq)]
+    vs = [W.normal(740 + b, (total[b], 1, d)) for b in range(n_seq)]
+    ref = [oracle.unsharded_causal(W.to_f64(qs[b]), W.to_f64(ks[b]), W.to_f64(vs[b]))
+           for b in range(n_seq)]
+
+    def fresh_caches():
+        caches = [B.KVCache(cap, 1, d) for _ in range(n)]
+        for b in range(n_seq):
+            for r in range(n):
+                pos = B.cp_shard_positions(first[b], n, r).astype(np.int64)
+                cu_new = np.zeros(n_seq + 1, dtype=np.int32)
+                cu_new[b + 1:] = len(pos)
+                B.cp_kv_append(caches[r], dev(ks[b][pos]), dev(vs[b][pos]), i32(pos), i32(cu_new))
+        return caches
+
+    # With n_seq a multiple of n every rank owns n_seq / n tokens at every iteration, so the
+    # shapes of a step do not change; which sequences they are does (round-robin), and that
+    # lives in device buffers the graph reads: bid, q_pos, cu_seqlens_new, the new rows.
+    per = n_seq // n
+    bufs = [dict(q=torch.zeros((per, nh, d), dtype=torch.bfloat16, device="cuda"),
+                 k=torch.zeros((per, 1, d), dtype=torch.bfloat16, device="cuda"),
+                 v=torch.zeros((per, 1, d), dtype=torch.bfloat16, device="cuda"),
+                 pos=torch.zeros(per, dtype=torch.int32, device="cuda"),
+                 bid=torch.zeros(per, dtype=torch.int32, device="cuda"),
+                 cu_new=torch.zeros(n_seq + 1, dtype=torch.int32, device="cuda"))
+            for _ in range(n)]
+
+    def stage(t):
+        owned = [[b for b in range(n_seq) if B.cp_decode_owner(b, t, n) == r] for r in range(n)]
+        for r in range(n):
+            bs = owned[r]
+            p = [first[b] + t for b in bs]
+            bufs[r]["q"].copy_(torch.cat([qs[b][x:x + 1] for b, x in zip(bs, p)]))
+            bufs[r]["k"].copy_(torch.cat([ks[b][x:x + 1] for b, x in zip(bs, p)]))
+            bufs[r]["v"].copy_(torch.cat([vs[b][x:x + 1] for b, x in zip(bs, p)]))
+            bufs[r]["pos"].copy_(i32(p))
+            bufs[r]["bid"].copy_(i32(bs))
+            counts = np.zeros(n_seq, dtype=np.int64)
+            counts[bs] = 1
+            bufs[r]["cu_new"].copy_(i32(np.concatenate([[0], np.cumsum(counts)])))
+        return owned
+
+    def make_step(caches):
+        ring = B.Ring([x["q"] for x in bufs], [c.k for c in caches], [c.v for c in caches],
+                      [x["pos"] for x in bufs], [c.kv_pos for c in caches],
+                      out_dtype=torch.float32, cu_seqlens_kv=[c.cu for c in caches],
+                      bid=[x["bid"] for x in bufs])
+
+        def step():
+            for r in range(n):
+                B.cp_kv_append(caches[r], bufs[r]["k"], bufs[r]["v"], bufs[r]["pos"],
+                               bufs[r]["cu_new"])
+            B.cp_ring_passq_decode(ring)
+        return ring, step
+
+    # eager run: the expected outputs of every step
+    caches = fresh_caches()
+    ring, step = make_step(caches)
+    eager = []
+    for t in range(n_steps):
+        owned = stage(t)
+        step()
+        torch.cuda.synchronize()
+        eager.append(([o.clone() for o in ring.out], [l.clone() for l in ring.lse]))
+        for r in range(n):
+            for i, b in enumerate(owned[r]):
+                p = first[b] + t
+                check(ring.out[r][i:i + 1], ring.lse[r][i:i + 1], ref[b][0][p:p + 1],
+                      ref[b][1][p:p + 1], what="eager step %d seq %d" % (t, b))
+    eager_used = [c.used.cpu().numpy().copy() for c in caches]
+
+    # the same steps from one graph over fresh caches
+    caches = fresh_caches()
+    ring, step = make_step(caches)
+    stage(0)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        g.capture_begin(capture_error_mode="relaxed")
+        step()
+        g.capture_end()
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 20, device="cuda")
+    for t in range(n_steps):
+        stage(t)                       # eager copies into the graph's input buffers
+        scratch.add_(1.0)              # unrelated eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for r in range(n):
+            assert torch.equal(ring.out[r], eager[t][0][r]), "replay %d rank %d" % (t, r)
+            assert torch.equal(ring.lse[r], eager[t][1][r]), "replay %d rank %d" % (t, r)
+    for r in range(n):
+        np.testing.assert_array_equal(caches[r].used.cpu().numpy(), eager_used[r])
+        assert int(caches[r].dropped.item()) == 0
+        assert caches[r].used.cpu().numpy()[:-1].sum() == \
+            sum(len(B.cp_shard_positions(L, n, r)) for L in first) + n_steps * per
