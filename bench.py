@@ -3,14 +3,16 @@
 
 One "step" is one pass of the whole hot path over one batch of synthetic input: for the
 default workload (Llama3-405B per-GPU head shape, 128K full prefill, pass-KV) that is the
-complete ring of Algorithm 2 over all 16 virtual CP ranks: 16 x 16 partial-attention calls
-on load-balanced shards, each merging its result into the rank's running (O, LSE) in its
-epilogue (Equation 4; `aux` also times the variant with 16 stored partials and a separate
-merge kernel per rank). Inputs are resident in HBM before the timed region.
+complete ring of Algorithm 2 over all 16 virtual CP ranks: every rank's queries against the
+16 load-balanced KV shards in ring order, merged with Equation 4. The headline runs a rank's
+16 ring steps inside one launch (running softmax state in registers, every shard behind an
+arrival flag); `aux` also times a launch per ring step with the merge in the attention
+epilogues, and with 16 stored partials and a separate merge kernel per rank. Inputs are
+resident in HBM before the timed region.
 
 Prints ONE JSON line. `value` is causal-effective TFLOP/s (4 * d * N_H * visible pairs).
-`roofline` describes the dominant kernel (the bf16 MFMA partial-attention kernel), timed
-with HIP events around the plain partial-attention calls of every rank in a second pass.
+`roofline` describes the dominant kernel (the bf16 MFMA attention kernel walking a rank's
+ring), timed with HIP events around whole driver calls in a second pass.
 `cpu_baseline` times the fp64 oracle on a bounded sample of the same workload.
 `aux` carries the bandwidth-bound parts (merge, split-KV decode) in GB/s.
 """
@@ -59,13 +61,18 @@ def build_prefill(w: W.Workload):
     vs = [v[i].contiguous() for i in idx]
     del q
     ps = [_i32(p) for p in pos]
-    # The merge (Equation 4) runs in the attention epilogues: one running fp32 (O, LSE) per rank.
-    # One stream: with the drivers' optional second stream consecutive launches overlap, which
-    # gains under 1 % here and makes per-kernel durations in a trace meaningless.
-    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, fused_merge=True)
+    # Headline: every rank's N ring steps walked inside ONE launch (running softmax state in
+    # registers, so Equation 4 is applied inside the online softmax; shards visited in ring
+    # order, each behind its arrival flag - all set here, the shards being resident).
+    flags = [torch.ones(n, dtype=torch.int32, device="cuda") for _ in range(n)]
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, fused_merge=2, arrived=flags)
+    # one launch per ring step, the merge in the attention epilogues (one running fp32 (O, LSE)
+    # per rank). One stream: with the drivers' optional second stream consecutive launches
+    # overlap, which gains under 1 % here and makes per-kernel durations in a trace meaningless.
+    steps = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, fused_merge=True)
     # scratch for the per-call measurements: 16 fp32 partials and their separate merge
     parts = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, part_dtype=torch.float32)
-    return dict(ring=ring, parts=parts, pos=pos, qs=qs, ks=ks, vs=vs, ps=ps, k_full=k, v_full=v)
+    return dict(ring=ring, steps=steps, parts=parts, pos=pos, qs=qs, ks=ks, vs=vs, ps=ps, k_full=k, v_full=v)
 
 
 def time_steps(fn, steps: int, warmup: int) -> float:
@@ -379,15 +386,18 @@ def hbm_read_probe(nbytes: int, n_buffers: int = 16, reps: int = 5):
     return out
 
 
-def pmc_probe(ring):
+def pmc_probe(st):
     """The work the counter runs profile: a streaming kernel that reads and writes
-    PROBE_COPY_BYTES (the scale reference), one pass-KV ring pass, one decode pass."""
+    PROBE_COPY_BYTES (the scale reference), one pass-KV ring pass in one launch per rank, one
+    with a launch per step and stored partials (and their merge), one decode pass."""
     src = torch.ones(PROBE_COPY_BYTES // 4, dtype=torch.float32, device="cuda")
     dst = torch.empty_like(src)
     for _ in range(3):
         torch.mul(src, 2.0, out=dst)
     torch.cuda.synchronize()
-    B.cp_ring_passkv(ring)
+    B.cp_ring_passkv(st["ring"])
+    torch.cuda.synchronize()
+    B.cp_ring_passkv(st["parts"])
     torch.cuda.synchronize()
     bench_decode(W.WORKLOADS["decode_b32"], reps=1)
     print("pmc probe done")
@@ -431,15 +441,27 @@ def main():
     st = build_prefill(w)
     ring = st["ring"]
     if args.pmc_probe:
-        pmc_probe(st["parts"])
+        pmc_probe(st)
         return
     sec = time_steps(lambda: B.cp_ring_passkv(ring), args.steps, args.warmup)
     t = w.t_new
     flop_step = 4.0 * w.head_dim * w.n_q_heads * (t * (t + 1) // 2)
     tflops = flop_step / sec / 1e12
 
+    # dominant kernel: the ring walk, one launch per rank; HIP events around a whole driver call
+    # (16 launches and the 16 tile-bound pre-passes, 3.5 us each), repeated `steps` times
+    walk_ms = []
+    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.cp_ring_passkv(ring)
+        e1.record()
+        torch.cuda.synchronize()
+        walk_ms.append(e0.elapsed_time(e1))
+    ms_per_launch = float(np.mean(walk_ms)) / w.n_ranks
+    flop_per_launch = flop_step / w.n_ranks     # every rank sees the same number of pairs
+    achieved = flop_per_launch / (ms_per_launch * 1e-3) / 1e12
     kp = kernel_pass_prefill(w, st, ranks=list(range(w.n_ranks)))
-    achieved = kp["flop_per_launch"] / (kp["ms_per_launch"] * 1e-3) / 1e12
     result = {
         "metric": "per-rank partial-attn+merge TFLOP/s (% bf16 MFMA peak); decode HBM GB/s",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -447,25 +469,34 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "order": "pass-KV", "virtual_ranks": w.n_ranks,
                    "tokens": t, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
-                   "head_dim": w.head_dim, "merge": "in the attention epilogues, fp32 running result",
+                   "head_dim": w.head_dim,
+                   "launches": "one per rank: its 16 ring steps are walked inside the kernel, "
+                               "each shard behind an arrival flag (all set: shards resident)",
+                   "merge": "Equation 4 inside the online softmax (running state in registers)",
                    "flops": "causal-effective 4*d*N_H*pairs",
                    "ms_per_rank": round(sec * 1e3 / w.n_ranks, 3)},
         "frac_of_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
-        "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel",
+        "roofline": {"bound": "mfma", "kernel": "prefill_ring_walk_kernel",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": stored_traffic("prefill_mfma_kernel", w.name),
-                     "us_per_launch": round(kp["ms_per_launch"] * 1e3, 2),
-                     "flop_per_launch": kp["flop_per_launch"], "launches": kp["n_launch"]},
+                     "traffic": stored_traffic("prefill_ring_walk_kernel", w.name),
+                     "us_per_launch": round(ms_per_launch * 1e3, 2),
+                     "flop_per_launch": flop_per_launch, "launches": w.n_ranks * args.steps},
         "aux": {"merge": {"ms": round(kp["merge_ms"], 4),
                           "gbs": round(kp["merge_bytes"] / (kp["merge_ms"] * 1e-3) / 1e9, 1),
                           "frac_hbm": round(kp["merge_bytes"] / (kp["merge_ms"] * 1e-3) / 1e9 /
-                                            PEAK_HBM_GBS, 4)}},
+                                            PEAK_HBM_GBS, 4)},
+                # one cp_attn_partial launch per ring step (the kernel prefill_mfma_kernel)
+                "per_step_launch": {
+                    "us_per_launch": round(kp["ms_per_launch"] * 1e3, 2),
+                    "tflops": round(kp["flop_per_launch"] / (kp["ms_per_launch"] * 1e-3) / 1e12, 2),
+                    "flop_per_launch": kp["flop_per_launch"], "launches": kp["n_launch"],
+                    "traffic": stored_traffic("prefill_mfma_kernel", w.name)}},
     }
     result["aux"]["per_call"] = per_call_prefill(w, st)
     if not args.no_aux and w.name == "prefill_128k":
-        # the same ring with bf16 partial outputs (the width the paper's All2All model assumes);
-        # the headline keeps fp32 partials
+        # a launch per ring step with stored partials and the merge kernel: fp32 partials, and
+        # bf16 partials (the width the paper's All2All model assumes)
         parts = st["parts"]
         secp = time_steps(lambda: B.cp_ring_passkv(parts), args.steps, args.warmup)
         result["aux"]["ring_separate_merge_fp32_partials"] = {
@@ -478,6 +509,44 @@ def main():
             "tflops": round(flop_step / sec16 / 1e12, 2),
             "ms_per_rank": round(sec16 * 1e3 / w.n_ranks, 3)}
         del ring16
+        # one launch per ring step, Equation 4 in the attention epilogues
+        stp = st["steps"]
+        secs = time_steps(lambda: B.cp_ring_passkv(stp), args.steps, args.warmup)
+        result["aux"]["ring_launch_per_step_merge_in_epilogues"] = {
+            "tflops": round(flop_step / secs / 1e12, 2),
+            "ms_per_rank": round(secs * 1e3 / w.n_ranks, 3),
+            "max_abs_diff_vs_headline": round(max(
+                float((a.float() - b.float()).abs().max()) for a, b in zip(stp.out, ring.out)), 5)}
+        # the headline's walk without arrival flags
+        walk = B.Ring(st["qs"], st["ks"], st["vs"], st["ps"], st["ps"], out_dtype=torch.bfloat16,
+                      fused_merge=2)
+        secw = time_steps(lambda: B.cp_ring_passkv(walk), args.steps, args.warmup)
+        result["aux"]["ring_walk_without_arrival_flags"] = {
+            "tflops": round(flop_step / secw / 1e12, 2),
+            "ms_per_rank": round(secw * 1e3 / w.n_ranks, 3)}
+        del walk
+        # context: the same per-rank result from ONE launch per rank over the whole sequence's
+        # K/V in natural order (what an all-gather of KV instead of a ring would run): no ring
+        # steps, so none of their per-launch start-up, epilogue and merge traffic
+        kv_pos_all = _i32(np.arange(w.t_new))
+        outs = [torch.empty_like(o) for o in ring.out]
+        lses = [torch.empty_like(l) for l in ring.lse]
+        ws_shape = B.make_shape(B.CP_BF16, w.head_dim, w.n_q_heads, w.n_kv_heads,
+                                st["qs"][0].shape[0], w.t_new)
+        ws_all = torch.empty(B.cp_workspace_bytes(ws_shape, B.CP_WS_PARTIAL) + 256,
+                             dtype=torch.uint8, device="cuda")
+
+        def all_kv():
+            for r in range(w.n_ranks):
+                B.cp_attn_partial(st["qs"][r], st["k_full"], st["v_full"], st["ps"][r],
+                                  kv_pos_all, out=outs[r], lse=lses[r], workspace=ws_all)
+        seca = time_steps(all_kv, args.steps, args.warmup)
+        result["aux"]["one_launch_per_rank_over_all_kv"] = {
+            "tflops": round(flop_step / seca / 1e12, 2),
+            "ms_per_rank": round(seca * 1e3 / w.n_ranks, 3),
+            "max_abs_diff_vs_headline": round(max(
+                float((a.float() - b.float()).abs().max()) for a, b in zip(outs, ring.out)), 5)}
+        del outs, lses, ws_all
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline_prefill(w, st)
     del st, ring

@@ -232,6 +232,11 @@ typedef struct {
    * slot 0, the following steps merge into it and the last one writes the rank's output.
    * One slot suffices; no merge pass. Requires part_dtype == CP_FP32, keep_partials == 0, no
    * decode, and calls that do not split their KV axis (else CP_ERR_UNSUPPORTED). 0: off.
+   * 2 (cp_ring_passkv only): one launch per rank walks the KV shards of all N ring steps in
+   * ring order with one running softmax state in registers, so Equation 4 is applied inside
+   * the online softmax and only the rank's output is written: no partials, no merge pass, no
+   * per-step launch. Same requirements as 1, and in addition all n_kv[k] equal and a multiple
+   * of 128 and n_ranks <= 32. See `arrived` below for how a step waits for its shard.
    */
   int32_t fused_merge;
   void* workspace; /* (device) max over ranks of the per-call workspace */
@@ -265,6 +270,23 @@ typedef struct {
    * permute or unpack pass.
    */
   int32_t message_layout;
+  /*
+   * fused_merge == 2 only. arrived: NULL (every shard is in place when the call is enqueued:
+   * the single-GPU simulation), or a (host) array of n_ranks (device) pointers; arrived[k]
+   * holds one int32 per ring step j of rank k, and the kernel reads the shard of step j
+   * (KV of rank (k - j) mod N) only once arrived[k][j] is nonzero: whatever moves the shard
+   * (a peer copy or receive on another stream) sets it afterwards. The kernel orders its
+   * reads of the shard after the flag but invalidates no cache, so every step's shard needs
+   * a buffer of its own that is complete before its flag is set and is not written again
+   * while the kernel runs (N receive buffers per rank instead of two). The wait is bounded:
+   * one thread per workgroup polls at most spin_limit (>= 1) times, a few hundred cycles
+   * apart; if the flag stays zero the workgroup leaves that shard out and sets *ring_error
+   * (device int32, required with arrived; the caller zeroes it) to 1 - the outputs are then
+   * not meaningful, but every kernel ends.
+   */
+  const int32_t* const* arrived;
+  int32_t* ring_error;
+  int32_t spin_limit;
 } cp_ring_desc;
 
 /* Bytes of one message of message_layout 1 (see cp_ring_desc); 0 for an invalid descriptor.

@@ -55,7 +55,8 @@ class cp_ring_desc(ctypes.Structure):
                 ("workspace", _vp), ("workspace_bytes", ctypes.c_size_t),
                 ("batch", _i32),
                 ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp)),
-                ("aux_stream", _vp), ("message_layout", _i32)]
+                ("aux_stream", _vp), ("message_layout", _i32),
+                ("arrived", ctypes.POINTER(_vp)), ("ring_error", _vp), ("spin_limit", _i32)]
 
 
 class cp_select_params(ctypes.Structure):
@@ -391,7 +392,8 @@ class Ring:
                  keep_partials: bool = False, softmax_scale: float = 0.0,
                  cu_seqlens_kv: Optional[List[torch.Tensor]] = None,
                  bid: Optional[List[torch.Tensor]] = None, aux_stream=None,
-                 fused_merge: bool = False, message_layout: bool = False):
+                 fused_merge=False, message_layout: bool = False,
+                 arrived: Optional[List[torch.Tensor]] = None, spin_limit: int = 1 << 20):
         n = len(q)
         self.n = n
         self.decode = cu_seqlens_kv is not None
@@ -439,7 +441,14 @@ class Ring:
         else:
             dsc.partial_out, dsc.partial_lse = _ptr(self.partial_out), _ptr(self.partial_lse)
         dsc.keep_partials = 1 if keep_partials else 0
-        dsc.fused_merge = 1 if fused_merge else 0
+        dsc.fused_merge = int(fused_merge)   # False/True, or 2: all steps of a rank in one launch
+        self.arrived = arrived
+        if arrived is not None:
+            self._arrived = (_vp * n)(*[_ptr(t) for t in arrived])
+            dsc.arrived = ctypes.cast(self._arrived, ctypes.POINTER(_vp))
+            self.ring_error = torch.zeros(1, dtype=torch.int32, device=dev)
+            dsc.ring_error = _ptr(self.ring_error)
+            dsc.spin_limit = spin_limit
         if self.decode:
             self._cu = (_vp * n)(*[_ptr(t) for t in cu_seqlens_kv])
             self._bid = (_vp * n)(*[(_ptr(t) if t.numel() > 0 else None) for t in bid])

@@ -220,13 +220,16 @@ int cp_attn_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* c
 static int check_ring(const cp_ring_desc* d, bool decode) {
   if (d == nullptr) return CP_ERR_NULL;
   if (d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS) return CP_ERR_SHAPE;
-  if (d->fused_merge != 0 && d->fused_merge != 1) return CP_ERR_SHAPE;
+  if (d->fused_merge < 0 || d->fused_merge > 2) return CP_ERR_SHAPE;
   if (d->message_layout != 0 && d->message_layout != 1) return CP_ERR_SHAPE;
   if (d->fused_merge && (decode || d->keep_partials || d->part_dtype != CP_FP32))
     return CP_ERR_UNSUPPORTED;
   if (d->n_q == nullptr || d->n_kv == nullptr || d->q == nullptr || d->k == nullptr ||
       d->v == nullptr || d->q_pos == nullptr || d->kv_pos == nullptr || d->out == nullptr)
     return CP_ERR_NULL;
+  if (d->fused_merge == 2 && d->arrived != nullptr &&
+      (d->ring_error == nullptr || d->spin_limit < 1))
+    return CP_ERR_SHAPE;
   if (d->partial_out == nullptr || (d->partial_lse == nullptr && !d->message_layout))
     return CP_ERR_NULL;
   if (d->part_dtype != CP_BF16 && d->part_dtype != CP_FP32) return CP_ERR_UNSUPPORTED;
@@ -395,6 +398,36 @@ int ring_rank_fused(const cp_ring_desc* d, const RingWork& w, const RingSlots& s
   return rc;
 }
 
+// fused_merge == 2: all ring steps of rank a in one launch (see launch_prefill_mfma_ring).
+// `kv_of_step(j)` names the KV rank of step j.
+template <typename KvOf>
+int ring_rank_walk(const cp_ring_desc* d, const RingWork& w, const RingSlots& slots, int a,
+                   int n, hipStream_t st, KvOf kv_of_step) {
+  if (d->n_q[a] == 0) return CP_OK;
+  if (!w.use_bounds) return CP_ERR_UNSUPPORTED;
+  const void* k[CP_MAX_PARTS];
+  const void* v[CP_MAX_PARTS];
+  const int32_t* pos[CP_MAX_PARTS];
+  const void* bounds[CP_MAX_PARTS];
+  for (int j = 0; j < n; ++j) {
+    const int s = kv_of_step(j);
+    if (d->n_kv[s] != d->n_kv[0]) return CP_ERR_UNSUPPORTED;  // equal shards only
+    if (!aligned16(d->k[s]) || !aligned16(d->v[s])) return CP_ERR_ALIGN;
+    k[j] = d->k[s]; v[j] = d->v[s]; pos[j] = d->kv_pos[s];
+    bounds[j] = (const char*)d->workspace + w.bounds_off[s];
+  }
+  if (!aligned16(d->q[a])) return CP_ERR_ALIGN;
+  const cp_shape s = ring_shape(d, a, 0, false);
+  if (!prefill_ring_walk_applies(s, n)) return CP_ERR_UNSUPPORTED;
+  const int32_t* arrived = d->arrived != nullptr ? d->arrived[a] : nullptr;
+  float* const lse_out = d->lse != nullptr ? d->lse[a] : nullptr;
+  return launch_prefill_mfma_ring(s, resolve_scale(s.softmax_scale, s.head_dim), d->q[a],
+                                  d->q_pos[a], n, k, v, pos, bounds, arrived, d->ring_error,
+                                  d->spin_limit, d->out[a],
+                                  lse_out != nullptr ? lse_out : slots.lse(0),  // LSE not wanted
+                                  d->out_dtype, st);
+}
+
 void ring_finish(RingWork& w) {
   if (w.dual) {
     (void)hipEventDestroy(w.fork);
@@ -483,6 +516,10 @@ int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
   if (rc != CP_OK) return rc;
   // Algorithm 2 as seen from each rank k in turn: N ring steps, then a local merge.
   for (int k = 0; k < n && rc == CP_OK; ++k) {
+    if (d->fused_merge == 2) {
+      rc = ring_rank_walk(d, w, slots, k, n, st, [&](int j) { return ((k - j) % n + n) % n; });
+      continue;
+    }
     if (d->fused_merge && n > 1) {
       rc = ring_rank_fused(d, w, slots, k, n, st, [&](int j) { return ((k - j) % n + n) % n; });
       continue;
@@ -501,6 +538,7 @@ int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
 static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
   int rc = check_ring(d, decode);
   if (rc != CP_OK) return rc;
+  if (d->fused_merge == 2) return CP_ERR_UNSUPPORTED;  // pass-KV only: the queries stay put
   hipStream_t st = (hipStream_t)stream;
   const RingSlots slots = make_slots(d);
   const int n = d->n_ranks;

@@ -26,6 +26,8 @@
 //     (grid.z); split results go to the workspace and are combined with Eq. 4.
 //   - The epilogue transposes the accumulators through LDS so that every output
 //     row leaves as one contiguous 512-byte (fp32) or 256-byte (bf16) run.
+#include <type_traits>
+
 #include "cp_common.h"
 
 namespace cp {
@@ -71,6 +73,27 @@ struct Params {
   int32_t n_splits;
   float scale_log2;       // softmax scale * log2(e)
 };
+
+// Ring walk in one launch (RING variant of prefill_mfma_kernel): the shards of a rank's ring
+// steps, in ring order. Passed by value (kernel argument segment), so a step's entry is a
+// scalar load with a uniform index.
+constexpr int kMaxRingShards = 32;
+struct RingShard {
+  const bf16_t* k;
+  const bf16_t* v;
+  const int32_t* kv_pos;
+  const int2* bounds;  // (min, max) of kv_pos per tile of this shard
+};
+struct RingTable {
+  RingShard shard[kMaxRingShards];
+  const int32_t* arrived;  // or NULL: [n_shards], nonzero once the shard of step j may be read
+  int32_t* error;          // set to 1 when a wait gave up (only used with `arrived`)
+  int32_t n_shards;
+  int32_t spin_limit;      // polls per shard before giving up
+};
+struct NoRing {};
+template <bool RING>
+using RingArg = typename std::conditional<RING, RingTable, NoRing>::type;
 
 __global__ __launch_bounds__(256) void kv_tile_bounds_kernel(const int32_t* __restrict__ kv_pos,
                                                               int32_t total_kv, int32_t n_tiles,
@@ -231,6 +254,58 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
     return launch_merge_strided(p.rows_all_heads, D, pl.n_splits, p.part_out, p.part_lse,
                                 p.rows_all_heads, out, out_dtype, lse, stream);
   return CP_OK;
+}
+
+bool prefill_ring_walk_applies(const cp_shape& s, int n_shards) {
+  if (n_shards < 1 || n_shards > kMaxRingShards) return false;
+  if (s.total_kv <= 0 || s.total_kv % TILE != 0) return false;
+  const Plan pl = make_plan(s);
+  return pl.n_row_blocks > 0 && pl.n_splits == 1;
+}
+
+int launch_prefill_mfma_ring(const cp_shape& s, float scale, const void* q, const int32_t* q_pos,
+                             int n_shards, const void* const* k, const void* const* v,
+                             const int32_t* const* kv_pos, const void* const* bounds,
+                             const int32_t* arrived, int32_t* error, int32_t spin_limit, void* out,
+                             float* lse, int32_t out_dtype, hipStream_t stream) {
+  if (!prefill_ring_walk_applies(s, n_shards)) return CP_ERR_UNSUPPORTED;
+  if (arrived != nullptr && (error == nullptr || spin_limit < 1)) return CP_ERR_SHAPE;
+  if (s.n_kv_heads > 65535) return CP_ERR_SHAPE;
+  if (s.total_q * (s.n_q_heads / s.n_kv_heads) > 0x7fffffffLL) return CP_ERR_SHAPE;  // 31-bit rows
+  const Plan pl = make_plan(s);
+  Params p = {};
+  p.q = (const bf16_t*)q; p.q_pos = q_pos;
+  p.k = (const bf16_t*)k[0]; p.v = (const bf16_t*)v[0]; p.kv_pos = kv_pos[0];
+  p.bounds = (const int2*)bounds[0];
+  p.out = out; p.lse = lse;
+  p.group = s.n_q_heads / s.n_kv_heads;
+  p.rows = s.total_q * p.group;
+  p.rows_all_heads = s.total_q * s.n_q_heads;
+  p.n_kv_heads = s.n_kv_heads;
+  p.total_kv = (int32_t)s.total_kv;
+  p.n_tiles = pl.n_tiles;
+  p.tiles_per_split = pl.tiles_per_split;
+  p.n_splits = 1;
+  p.scale_log2 = scale * kLog2e;
+  RingTable rt = {};
+  for (int j = 0; j < n_shards; ++j) {
+    if (k[j] == nullptr || v[j] == nullptr || kv_pos[j] == nullptr || bounds[j] == nullptr)
+      return CP_ERR_NULL;
+    rt.shard[j].k = (const bf16_t*)k[j];
+    rt.shard[j].v = (const bf16_t*)v[j];
+    rt.shard[j].kv_pos = kv_pos[j];
+    rt.shard[j].bounds = (const int2*)bounds[j];
+  }
+  rt.arrived = arrived; rt.error = error; rt.n_shards = n_shards; rt.spin_limit = spin_limit;
+  auto kern = out_dtype == CP_BF16 ? prefill_ring_walk_kernel<bf16_t>
+                                   : prefill_ring_walk_kernel<float>;
+  constexpr int kSmem = SMEM_BYTES8;
+  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          kSmem) != hipSuccess)
+    return CP_ERR_LAUNCH;
+  const dim3 grid(pl.n_row_blocks, s.n_kv_heads, 1);
+  hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), kSmem, stream, p, rt);
+  return check_launch();
 }
 
 }  // namespace cp

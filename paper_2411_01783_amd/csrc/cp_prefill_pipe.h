@@ -313,9 +313,72 @@ __device__ __forceinline__ void pipe_body(PipeRegs& R, const bf16x8_t (&qf)[8],
 // SPLIT: the launch splits the KV axis over grid.z and writes fp32 partials to the workspace.
 // ACC: the result is merged into a running (O, LSE) in the epilogue instead of being written
 // as a partial (Equation 4 applied step by step); see the epilogue.
-template <typename TO, bool BAND, bool SPLIT, bool ACC = false>
-__global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
-    Params p, const int2* __restrict__ tile_bounds) {
+// ---- ring walk (RING variant): per-shard pointers and the bounded wait for a shard ----
+__device__ __forceinline__ int ring_shards(const RingTable& ring) { return ring.n_shards; }
+__device__ __forceinline__ int ring_shards(const NoRing&) { return 1; }
+
+// Points the loader at the shard of ring step `shard`. With arrival flags, thread 0 makes
+// sure of the step's flag first: `peek` is what it read of that flag while the previous shard
+// was being walked (so a shard that arrived in time costs no round trip here); if that was
+// zero it polls (uncached loads, a short sleep between them, at most ring.spin_limit of them).
+// The whole workgroup learns the outcome through LDS; false = the flag never came up:
+// *ring.error is set and the caller leaves the shard out. Every wait ends.
+__device__ __forceinline__ int ring_flag(const RingTable& ring, int step) {
+  return __hip_atomic_load(ring.arrived + step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+__device__ __forceinline__ bool ring_enter(const RingTable& ring, int shard, int kvh, int tid,
+                                           int* wg_scratch, int& peek, const char*& k_head,
+                                           const char*& v_head, const int32_t*& kv_pos_cur,
+                                           const int2*& bounds_cur) {
+  const RingShard& e = ring.shard[shard];
+  k_head = (const char*)e.k + (int64_t)kvh * ROW_BYTES;
+  v_head = (const char*)e.v + (int64_t)kvh * ROW_BYTES;
+  kv_pos_cur = e.kv_pos;
+  bounds_cur = e.bounds;
+  if (ring.arrived == nullptr) return true;
+  int* const slot = wg_scratch + 20 + (shard & 1);  // two slots: a wavefront may lag one step
+  if (tid == 0) {
+    int ok = 1;
+    if (peek == 0) {
+      int budget = ring.spin_limit;
+      while (ring_flag(ring, shard) == 0) {
+        if (--budget <= 0) {
+          ok = 0;
+          break;
+        }
+        __builtin_amdgcn_s_sleep(32);
+      }
+    }
+    if (!ok) *ring.error = 1;
+    *slot = ok;
+    // a look at the next step's flag, used when the walk gets there
+    peek = shard + 1 < ring.n_shards ? ring_flag(ring, shard + 1) : 0;
+  }
+  lds_barrier();
+  const int ok = __builtin_amdgcn_readfirstlane(*slot);
+  // The shard's data is read after its flag: every load of it is issued after this barrier,
+  // which thread 0 reaches only with the flag's value in hand. No cache invalidation: the
+  // caller gives every step a buffer of its own that is complete before its flag is set and
+  // is not written again while the kernel runs, so no line of it can be in a cache before the
+  // flag is seen. (An agent-scope acquire here invalidates the XCD's L2 once per workgroup and
+  // shard and costs 3.5 % of the walk.)
+  return ok != 0;
+}
+__device__ __forceinline__ bool ring_enter(const NoRing&, int, int, int, int*, int&, const char*&,
+                                           const char*&, const int32_t*&, const int2*&) {
+  return true;
+}
+
+// RING: one launch walks the KV shards of all ring steps of a rank, in ring order, with one
+// running (O, l, m) in registers: the merge of Equation 4 happens inside the online softmax
+// and nothing but the rank's final output is written. `ring` names the shards (same size each,
+// a multiple of TILE) and, optionally, one arrival flag per step that the workgroup waits for
+// (bounded) before it touches the shard.
+template <typename TO, bool BAND, bool SPLIT, bool ACC, bool RING>
+__device__ __forceinline__ void prefill_body(const Params& p,
+                                             const int2* __restrict__ tile_bounds,
+                                             const RingArg<RING>& ring) {
+  static_assert(!RING || (!BAND && !SPLIT && !ACC), "the ring walk is its own variant");
   extern __shared__ __align__(16) char smem[];
   char* const kbuf0 = smem;
   char* const vbuf0 = smem + OFF_V8;
@@ -352,7 +415,9 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   const int t_begin = split * p.tiles_per_split;
   const int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
   int2 first_bounds = make_int2(0, 0);
-  if (t_begin + wave * 64 + lane < t_end) first_bounds = tile_bounds[t_begin + wave * 64 + lane];
+  const int2* bounds_cur = tile_bounds;
+  if constexpr (RING) bounds_cur = ring.shard[0].bounds;
+  if (t_begin + wave * 64 + lane < t_end) first_bounds = bounds_cur[t_begin + wave * 64 + lane];
 
   bf16x8_t qf[8];
 #pragma unroll
@@ -414,8 +479,10 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   const uint32_t stride_b = (uint32_t)p.n_kv_heads * ROW_BYTES;  // bytes between tokens
   const int l_row = lane >> 4, l_pos = lane & 15;
   const uint32_t v_chunk = (l_pos ^ ((l_row & 3) * 4)) * 16;
-  const char* const k_head = (const char*)p.k + (int64_t)kvh * ROW_BYTES;
-  const char* const v_head = (const char*)p.v + (int64_t)kvh * ROW_BYTES;
+  // (wave-uniform; the ring walk re-points them at every shard)
+  const char* k_head = (const char*)p.k + (int64_t)kvh * ROW_BYTES;
+  const char* v_head = (const char*)p.v + (int64_t)kvh * ROW_BYTES;
+  const int32_t* kv_pos_cur = p.kv_pos;
   auto issue_part = [&](auto ic, int key0, int b) __attribute__((always_inline)) {
     constexpr int I = decltype(ic)::value;
     const int row = wave * 16 + I * 4 + l_row;
@@ -432,7 +499,7 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
   auto load_pos = [&](int key0) -> int32_t {
     if (tid >= TILE) return 0;
     const int key = key0 + tid;
-    return key < total_kv ? p.kv_pos[key] : CP_POS_PAD_KV;
+    return key < total_kv ? kv_pos_cur[key] : CP_POS_PAD_KV;
   };
   // a tile pays for the mask when one of its keys can be hidden from one of this wavefront's
   // rows (this includes the tiles that only other wavefronts of the workgroup can see)
@@ -455,159 +522,168 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
                 (vq >> 1) * 16 + (vq & 1) * 8 + (db ^ vj) * 64;
   uint32_t paddr = smem_lds + OFF_POS8 + g * 16;
 
-  for (int c0 = t_begin; c0 < t_end; c0 += MAX_LIVE) {
-    // Compact the tiles some query of the workgroup can see (smallest key position not
-    // beyond the largest query position) into an ascending list in LDS: (tile, min, max).
-    lds_barrier();  // previous chunk (list, tile buffers) fully consumed
-    {
-      const int t = c0 + wave * 64 + lane;
-      int2 b = make_int2(0, 0);
-      bool lv = false;
-      if (t < t_end) {
-        b = c0 == t_begin ? first_bounds : tile_bounds[t];
-        lv = b.x <= wg_qmax && (!BAND || b.y >= wg_lomin);
+  const int n_shards = RING ? ring_shards(ring) : 1;
+  int flag_peek = 0;
+  for (int shard = 0; shard < n_shards; ++shard) {
+    if constexpr (RING) {
+      if (!ring_enter(ring, shard, kvh, tid, wg_scratch, flag_peek, k_head, v_head, kv_pos_cur,
+                      bounds_cur))
+        continue;  // the shard never arrived: reported through ring.error, walk goes on
+    }
+    for (int c0 = t_begin; c0 < t_end; c0 += MAX_LIVE) {
+      // Compact the tiles some query of the workgroup can see (smallest key position not
+      // beyond the largest query position) into an ascending list in LDS: (tile, min, max).
+      lds_barrier();  // previous chunk (list, tile buffers) fully consumed
+      {
+        const int t = c0 + wave * 64 + lane;
+        int2 b = make_int2(0, 0);
+        bool lv = false;
+        if (t < t_end) {
+          b = (c0 == t_begin && shard == 0) ? first_bounds : bounds_cur[t];
+          lv = b.x <= wg_qmax && (!BAND || b.y >= wg_lomin);
+        }
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(lv);
+        if (lane == 0) wg_scratch[wave] = __builtin_popcountll(mask);
+        lds_barrier();
+        int base = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < NWAVE; ++w) {
+          const int c = wg_scratch[w];
+          if (w < wave) base += c;
+          total += c;
+        }
+        if (lv)
+          live[base + __builtin_popcountll(mask & ((1ull << lane) - 1ull))] =
+              make_int4(t, b.x, b.y, 0);
+        if (tid == 0) wg_scratch[NWAVE] = total;
       }
-      const uint64_t mask = __builtin_amdgcn_ballot_w64(lv);
-      if (lane == 0) wg_scratch[wave] = __builtin_popcountll(mask);
       lds_barrier();
-      int base = 0, total = 0;
-#pragma unroll
-      for (int w = 0; w < NWAVE; ++w) {
-        const int c = wg_scratch[w];
-        if (w < wave) base += c;
-        total += c;
-      }
-      if (lv)
-        live[base + __builtin_popcountll(mask & ((1ull << lane) - 1ull))] =
-            make_int4(t, b.x, b.y, 0);
-      if (tid == 0) wg_scratch[NWAVE] = total;
-    }
-    lds_barrier();
-    const int n_live = __builtin_amdgcn_readfirstlane(wg_scratch[NWAVE]);
-    if (n_live == 0) continue;
+      const int n_live = __builtin_amdgcn_readfirstlane(wg_scratch[NWAVE]);
+      if (n_live == 0) continue;
 #ifdef CP_PIPE_STAMPS
-    t_p2 = __builtin_readcyclecounter();
+      t_p2 = __builtin_readcyclecounter();
 #endif
 
-    // ---- prologue: tile 0 into buffer 0, Q stage of block 0 ----
-    int32_t next_pos = 0;
-    bool need_mask, next_mask = false;
-    int next_key0 = 0;
-    auto read_entry = [&](int idx, int& key0, bool& mask_it) {
-      const int4 e = live[idx < n_live ? idx : n_live - 1];
-      const int tile = __builtin_amdgcn_readfirstlane(e.x);
-      key0 = tile * TILE;
-      mask_it = tile_needs_mask(tile, __builtin_amdgcn_readfirstlane(e.y),
-                                __builtin_amdgcn_readfirstlane(e.z));
-    };
-    {
-      int key0;
-      read_entry(0, key0, need_mask);
-      read_entry(1, next_key0, next_mask);
-      issue_part(IntC<0>{}, key0, 0);
-      issue_part(IntC<1>{}, key0, 0);
-      issue_part(IntC<2>{}, key0, 0);
-      issue_part(IntC<3>{}, key0, 0);
-      const int32_t pos = load_pos(key0);
-      if (tid < TILE) posbuf0[tid] = pos;
-      __syncthreads();  // waits for the tile (vmcnt) and publishes it
-#ifdef CP_PIPE_STAMPS
-      t_p3 = __builtin_readcyclecounter();
-#endif
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) R.kf[ks] = lds_read_b128<0>(kaddr[ks]);
-      lgkm_wait<0>(R.kf[0], R.kf[1], R.kf[2], R.kf[3]);
-      lgkm_wait<0>(R.kf[4], R.kf[5], R.kf[6], R.kf[7]);
-#pragma unroll
-      for (int i = 0; i < 16; ++i) R.s[0][i] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
-        R.s[0] = mfma32(__builtin_bit_cast(bf16x8_t, R.kf[ks]), qf[ks], R.s[0]);
-      __builtin_amdgcn_sched_barrier(0);
-      // stand-in V fragments for the empty P stage of the first step (finite data, P = 0)
-#pragma unroll
-      for (int m = 0; m < 8; ++m) R.vf[m] = lds_read_vt_frag<0>(vaddr[m & 3]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) R.pb[1][0][i] = R.pb[1][1][i] = 0u;
-      __builtin_amdgcn_sched_barrier(0);
-    }
-
-    auto no_hook = [](auto) {};
-#ifdef CP_PIPE_STAMPS
-    unsigned long long st[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    unsigned long long t_prev = __builtin_readcyclecounter();
-    t_loop0 = t_prev;
-#endif
-    for (int it = 0; it < n_live; ++it) {
-      const bool has_next = it + 1 < n_live;
-      const int nb = (it + 1) & 1;
-      CP_STAMP(5);
-      // The next tile is requested during the first two steps, one part (a K and a V
-      // instruction per wavefront) at a time: a burst of all eight fills the memory pipeline's
-      // queue and stalls every wavefront behind it.
-      pipe_body<0, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref,
-                         [&](auto mc) __attribute__((always_inline)) {
-                           constexpr int M = decltype(mc)::value;
-                           if (M == 1 && __builtin_expect(has_next, 1)) issue_part(IntC<0>{}, next_key0, nb);
-                           if (M == 9 && __builtin_expect(has_next, 1)) issue_part(IntC<1>{}, next_key0, nb);
-                         });
-      pipe_body<1, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref,
-                         [&](auto mc) __attribute__((always_inline)) {
-                           constexpr int M = decltype(mc)::value;
-                           if (M == 1 && __builtin_expect(has_next, 1)) issue_part(IntC<2>{}, next_key0, nb);
-                           if (M == 9 && __builtin_expect(has_next, 1)) {
-                             issue_part(IntC<3>{}, next_key0, nb);
-                             next_pos = load_pos(next_key0);
-                           }
-                         });
-      pipe_body<2, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref, no_hook);
-      // barrier Y: the next tile has landed in every wavefront
-      CP_STAMP(0);
-      __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-      CP_STAMP(1);
-      if (has_next && tid < TILE) posbuf0[nb * TILE + tid] = next_pos;
-      const bool cur_mask = need_mask;
-      need_mask = next_mask;
-      read_entry(it + 2, next_key0, next_mask);  // no direct-to-LDS load is in flight here
-      __syncthreads();
-      CP_STAMP(2);
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) kaddr[ks] ^= KD_BYTES;  // K of the next tile from here on
-      pipe_body<3, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, cur_mask, have_ref, no_hook);
-      // barrier X: every LDS read of this tile has completed; its buffers may be refilled
-      __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-      CP_STAMP(3);
-      __syncthreads();
-      CP_STAMP(4);
-#pragma unroll
-      for (int db = 0; db < 4; ++db) vaddr[db] ^= KD_BYTES;
-      paddr ^= POS_BYTES;
-    }
-
-    // ---- drain: P stage of the last block ----
-    {
-      auto last = [&](auto mc) __attribute__((always_inline)) {
-        constexpr int M = decltype(mc)::value;
-        lgkm_wait<14 - 2 * M>(R.vf[M]);
-        R.o[M & 3] = mfma32(__builtin_bit_cast(bf16x8_t, R.vf[M]),
-                            __builtin_bit_cast(bf16x8_t, R.pb[1][M >> 2]), R.o[M & 3]);
+      // ---- prologue: tile 0 into buffer 0, Q stage of block 0 ----
+      int32_t next_pos = 0;
+      bool need_mask, next_mask = false;
+      int next_key0 = 0;
+      auto read_entry = [&](int idx, int& key0, bool& mask_it) {
+        const int4 e = live[idx < n_live ? idx : n_live - 1];
+        const int tile = __builtin_amdgcn_readfirstlane(e.x);
+        key0 = tile * TILE;
+        mask_it = tile_needs_mask(tile, __builtin_amdgcn_readfirstlane(e.y),
+                                  __builtin_amdgcn_readfirstlane(e.z));
       };
-      last(IntC<0>{}); last(IntC<1>{}); last(IntC<2>{}); last(IntC<3>{});
-      last(IntC<4>{}); last(IntC<5>{}); last(IntC<6>{}); last(IntC<7>{});
-      __builtin_amdgcn_sched_barrier(0);
-    }
+      {
+        int key0;
+        read_entry(0, key0, need_mask);
+        read_entry(1, next_key0, next_mask);
+        issue_part(IntC<0>{}, key0, 0);
+        issue_part(IntC<1>{}, key0, 0);
+        issue_part(IntC<2>{}, key0, 0);
+        issue_part(IntC<3>{}, key0, 0);
+        const int32_t pos = load_pos(key0);
+        if (tid < TILE) posbuf0[tid] = pos;
+        __syncthreads();  // waits for the tile (vmcnt) and publishes it
 #ifdef CP_PIPE_STAMPS
-    if (lane == 0 && split == 0 && kvh == 0 && blockIdx.x < 1024)
-      for (int i = 0; i < 8; ++i) cp_dbg[(blockIdx.x * 8 + wave) * 8 + i] = i == 7 ? (unsigned long long)n_live : st[i];
-    t_loop1 = __builtin_readcyclecounter();
+        t_p3 = __builtin_readcyclecounter();
 #endif
-    // back to buffer-0 addressing for the next chunk
-    if (n_live & 1) {
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) kaddr[ks] ^= KD_BYTES;
+        for (int ks = 0; ks < 8; ++ks) R.kf[ks] = lds_read_b128<0>(kaddr[ks]);
+        lgkm_wait<0>(R.kf[0], R.kf[1], R.kf[2], R.kf[3]);
+        lgkm_wait<0>(R.kf[4], R.kf[5], R.kf[6], R.kf[7]);
 #pragma unroll
-      for (int db = 0; db < 4; ++db) vaddr[db] ^= KD_BYTES;
-      paddr ^= POS_BYTES;
+        for (int i = 0; i < 16; ++i) R.s[0][i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+          R.s[0] = mfma32(__builtin_bit_cast(bf16x8_t, R.kf[ks]), qf[ks], R.s[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        // stand-in V fragments for the empty P stage of the first step (finite data, P = 0)
+#pragma unroll
+        for (int m = 0; m < 8; ++m) R.vf[m] = lds_read_vt_frag<0>(vaddr[m & 3]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) R.pb[1][0][i] = R.pb[1][1][i] = 0u;
+        __builtin_amdgcn_sched_barrier(0);
+      }
+
+      auto no_hook = [](auto) {};
+#ifdef CP_PIPE_STAMPS
+      unsigned long long st[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      unsigned long long t_prev = __builtin_readcyclecounter();
+      t_loop0 = t_prev;
+#endif
+      for (int it = 0; it < n_live; ++it) {
+        const bool has_next = it + 1 < n_live;
+        const int nb = (it + 1) & 1;
+        CP_STAMP(5);
+        // The next tile is requested during the first two steps, one part (a K and a V
+        // instruction per wavefront) at a time: a burst of all eight fills the memory pipeline's
+        // queue and stalls every wavefront behind it.
+        pipe_body<0, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref,
+                           [&](auto mc) __attribute__((always_inline)) {
+                             constexpr int M = decltype(mc)::value;
+                             if (M == 1 && __builtin_expect(has_next, 1)) issue_part(IntC<0>{}, next_key0, nb);
+                             if (M == 9 && __builtin_expect(has_next, 1)) issue_part(IntC<1>{}, next_key0, nb);
+                           });
+        pipe_body<1, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref,
+                           [&](auto mc) __attribute__((always_inline)) {
+                             constexpr int M = decltype(mc)::value;
+                             if (M == 1 && __builtin_expect(has_next, 1)) issue_part(IntC<2>{}, next_key0, nb);
+                             if (M == 9 && __builtin_expect(has_next, 1)) {
+                               issue_part(IntC<3>{}, next_key0, nb);
+                               next_pos = load_pos(next_key0);
+                             }
+                           });
+        pipe_body<2, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref, no_hook);
+        // barrier Y: the next tile has landed in every wavefront
+        CP_STAMP(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        CP_STAMP(1);
+        if (has_next && tid < TILE) posbuf0[nb * TILE + tid] = next_pos;
+        const bool cur_mask = need_mask;
+        need_mask = next_mask;
+        read_entry(it + 2, next_key0, next_mask);  // no direct-to-LDS load is in flight here
+        __syncthreads();
+        CP_STAMP(2);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kaddr[ks] ^= KD_BYTES;  // K of the next tile from here on
+        pipe_body<3, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, cur_mask, have_ref, no_hook);
+        // barrier X: every LDS read of this tile has completed; its buffers may be refilled
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+        CP_STAMP(3);
+        __syncthreads();
+        CP_STAMP(4);
+#pragma unroll
+        for (int db = 0; db < 4; ++db) vaddr[db] ^= KD_BYTES;
+        paddr ^= POS_BYTES;
+      }
+
+      // ---- drain: P stage of the last block ----
+      {
+        auto last = [&](auto mc) __attribute__((always_inline)) {
+          constexpr int M = decltype(mc)::value;
+          lgkm_wait<14 - 2 * M>(R.vf[M]);
+          R.o[M & 3] = mfma32(__builtin_bit_cast(bf16x8_t, R.vf[M]),
+                              __builtin_bit_cast(bf16x8_t, R.pb[1][M >> 2]), R.o[M & 3]);
+        };
+        last(IntC<0>{}); last(IntC<1>{}); last(IntC<2>{}); last(IntC<3>{});
+        last(IntC<4>{}); last(IntC<5>{}); last(IntC<6>{}); last(IntC<7>{});
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#ifdef CP_PIPE_STAMPS
+      if (lane == 0 && split == 0 && kvh == 0 && blockIdx.x < 1024)
+        for (int i = 0; i < 8; ++i) cp_dbg[(blockIdx.x * 8 + wave) * 8 + i] = i == 7 ? (unsigned long long)n_live : st[i];
+      t_loop1 = __builtin_readcyclecounter();
+#endif
+      // back to buffer-0 addressing for the next chunk
+      if (n_live & 1) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) kaddr[ks] ^= KD_BYTES;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) vaddr[db] ^= KD_BYTES;
+        paddr ^= POS_BYTES;
+      }
     }
   }
 
@@ -737,4 +813,17 @@ __global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
     d2[4] = t_p1 - t_entry; d2[5] = t_p2 - t_p1; d2[6] = t_p3 - t_p2; d2[7] = t_loop0 - t_p3;
   }
 #endif
+}
+
+template <typename TO, bool BAND, bool SPLIT, bool ACC = false>
+__global__ __launch_bounds__(NTHREADS) void prefill_mfma_kernel(
+    const Params p, const int2* __restrict__ tile_bounds) {
+  prefill_body<TO, BAND, SPLIT, ACC, false>(p, tile_bounds, NoRing{});
+}
+
+// All ring steps of a rank in one launch (the RING variant of the body).
+template <typename TO>
+__global__ __launch_bounds__(NTHREADS) void prefill_ring_walk_kernel(const Params p,
+                                                                     const RingTable ring) {
+  prefill_body<TO, false, false, false, true>(p, p.bounds, ring);
 }

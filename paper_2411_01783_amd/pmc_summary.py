@@ -15,7 +15,8 @@ import os
 import sys
 
 # kernel-name substring -> tag of the summary file (first match wins)
-KERNELS = [("prefill_mfma_kernel", "prefill_mfma_kernel"), ("decode_kernel", "decode_kernel"),
+KERNELS = [("prefill_ring_walk_kernel", "prefill_ring_walk_kernel"),
+           ("prefill_mfma_kernel", "prefill_mfma_kernel"), ("decode_kernel", "decode_kernel"),
            ("merge_split_kernel", "merge_kernel_split"), ("merge_kernel", "merge_kernel_ring")]
 COPY_MARK = "MulFunctor"
 

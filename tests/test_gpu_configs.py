@@ -35,10 +35,10 @@ def _shard(w, q, k, v):
         [v[i].contiguous() for i in idx]
 
 
-@pytest.mark.parametrize("fused_merge", [True, False])
+@pytest.mark.parametrize("fused_merge", [2, True, False])
 def test_prefill_128k_passkv_ring_sampled(oracle, fused_merge):
-    # fused_merge=True is the configuration bench.py times; False keeps 16 partials per rank
-    # and merges them with the merge kernel
+    # 2 walks a rank's 16 ring steps in one launch; True merges in the epilogues of 16
+    # launches; False keeps 16 partials per rank and merges them with the merge kernel
     w = W.WORKLOADS["prefill_128k"]
     q, k, v = W.qkv(w, device="cuda")
     pos, qs, ks, vs = _shard(w, q, k, v)

@@ -241,6 +241,74 @@ def test_ring_fused_merge_matches_unsharded(oracle):
         B.cp_ring_passkv(small)
 
 
+@pytest.mark.parametrize("n,t,flags", [(4, 8192, False), (4, 8192, True), (3, 6144 + 3 * 256, False)])
+def test_ring_walk_in_one_launch_matches_unsharded(oracle, n, t, flags):
+    """fused_merge=2: every rank's N ring steps in one launch, with and without arrival
+    flags (all set before the call), fp32 and bf16 outputs, with and without the LSE."""
+    q, q64 = randn(51, (t, 16, 128))
+    k, k64 = randn(52, (t, 1, 128))
+    v, v64 = randn(53, (t, 1, 128))
+    pos = [B.cp_shard_positions(t, n, r) for r in range(n)]
+    assert len({len(p) for p in pos}) == 1 and len(pos[0]) % 128 == 0
+    rows = np.r_[0:48, t // 4 - 6:t // 4 + 6, t // 2 - 5:t // 2 + 5, t - 3 * t // 8:t - 3 * t // 8 + 16,
+                 t - 48:t]
+    ref_o, ref_l = oracle.attn(q64[rows], k64, v64, rows, np.arange(t))
+    where = {int(p): (a, i) for a in range(n) for i, p in enumerate(pos[a])}
+    for odt in (torch.float32, torch.bfloat16):
+        arrived = [torch.ones(n, dtype=torch.int32, device="cuda") for _ in range(n)] \
+            if flags else None
+        ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                      [i32(p) for p in pos], [i32(p) for p in pos], out_dtype=odt,
+                      fused_merge=2, arrived=arrived, spin_limit=1000)
+        out, lse = B.cp_ring_passkv(ring)
+        torch.cuda.synchronize()
+        if flags:
+            assert int(ring.ring_error.item()) == 0
+        got_o = torch.stack([out[where[int(r)][0]][where[int(r)][1]] for r in rows])
+        got_l = torch.stack([lse[where[int(r)][0]][where[int(r)][1]] for r in rows])
+        check(got_o, got_l, ref_o, ref_l, what="ring walk, %s" % odt)
+        # the step-by-step ring with the merge in the epilogues computes the same thing
+        if odt == torch.float32:
+            step = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos],
+                          [dev(v[p]) for p in pos], [i32(p) for p in pos], [i32(p) for p in pos],
+                          out_dtype=odt, fused_merge=True)
+            out_s, lse_s = B.cp_ring_passkv(step)
+            torch.cuda.synchronize()
+            for a in range(n):
+                assert float((out[a] - out_s[a]).abs().max()) < 2e-3
+                assert float((lse[a] - lse_s[a]).abs().max()) < 1e-4
+    with pytest.raises(B.CpError):   # pass-Q moves the queries: no such walk
+        B.cp_ring_passq(ring)
+
+
+def test_ring_walk_gives_up_on_a_shard_that_never_arrives(oracle):
+    """The host never sets one step's flag and allows three polls: every kernel still ends,
+    the error word is set, and the ranks whose flags were all set are unaffected."""
+    n, t = 4, 8192
+    q, q64 = randn(51, (t, 16, 128))
+    k, k64 = randn(52, (t, 1, 128))
+    v, v64 = randn(53, (t, 1, 128))
+    pos = [B.cp_shard_positions(t, n, r) for r in range(n)]
+    arrived = [torch.ones(n, dtype=torch.int32, device="cuda") for _ in range(n)]
+    arrived[2][1] = 0          # rank 2 never receives the shard of its step 1
+    ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
+                  [i32(p) for p in pos], [i32(p) for p in pos], out_dtype=torch.float32,
+                  fused_merge=2, arrived=arrived, spin_limit=3)
+    out, lse = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    assert int(ring.ring_error.item()) == 1
+    rows = np.r_[0:16, 1000:1016, 2032:2048]
+    for a in (0, 1, 3):
+        tok = pos[a][rows]
+        ref_o, ref_l = oracle.attn(q64[tok], k64, v64, tok, np.arange(t))
+        check(out[a][rows], lse[a][rows], ref_o, ref_l, what="rank %d" % a)
+    # rank 2 computed attention over everything but the missing shard (KV of rank 1)
+    keep = np.concatenate([pos[s] for s in (0, 2, 3)])
+    tok = pos[2][rows]
+    ref_o, ref_l = oracle.attn(q64[tok], k64[keep], v64[keep], tok, keep)
+    check(out[2][rows], lse[2][rows], ref_o, ref_l, what="rank 2 without the shard of rank 1")
+
+
 @pytest.mark.parametrize("n,t,two_streams", [(4, 2048, False), (3, 1000, False),
                                              (4, 2048, True), (2, 16384, True)])
 def test_mfma_load_balanced_partials_and_merge(oracle, n, t, two_streams):
