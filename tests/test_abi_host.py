@@ -238,6 +238,9 @@ def test_ring_descriptor_validation(lib):
     d.message_layout = 2
     assert lib.cp_ring_passkv(ctypes.byref(d), None) == -2
     d.message_layout = 0
+    d.fused_merge = 3
+    assert lib.cp_ring_passkv(ctypes.byref(d), None) == -2
+    d.fused_merge = 0
 
 
 def test_ring_message_bytes(lib):
