@@ -218,6 +218,21 @@ def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False):
     res = dict(workload=w.name, ms_per_rank=sec * 1e3 / n, gbs=(kv_bytes + io_bytes) / sec / 1e9,
                frac_hbm=(kv_bytes + io_bytes) / sec / 1e9 / PEAK_HBM_GBS,
                kv_mb_per_rank=kv_bytes / n / 1e6)
+    # All of Algorithm 4 through the driver, queries gathered: 16 decode calls (one per KV
+    # holder, all 32 queries) and the merge across holders of every query's 16 partials
+    order = np.argsort(np.arange(w.batch) % n, kind="stable")   # rank r owns b with b % n == r
+    per = w.batch // n
+    q_g, qpos_g, bid_g = st["q"][order].contiguous(), st["q_pos"][order].contiguous(), _i32(order)
+    sl = [slice(r * per, (r + 1) * per) for r in range(n)]
+    gring = B.Ring([q_g[x] for x in sl], [r["k"] for r in st["ranks"]],
+                   [r["v"] for r in st["ranks"]], [qpos_g[x] for x in sl],
+                   [r["kv_pos"] for r in st["ranks"]], out_dtype=torch.float32,
+                   keep_partials=True, gathered_q=True,
+                   cu_seqlens_kv=[r["cu"] for r in st["ranks"]], bid=[bid_g[x] for x in sl])
+    rsec = time_steps(lambda: B.cp_ring_passq_decode(gring), reps, 3)
+    res["ring_ms_per_rank"] = rsec * 1e3 / n
+    res["ring_gbs"] = (kv_bytes + io_bytes) / rsec / 1e9
+    del gring
     if graph:
         # the same 16-rank sequence replayed from one HIP graph (the paper runs decode under
         # graphs, Section 4.3); the library records kernels only, no memset nodes
@@ -314,6 +329,22 @@ def bench_partial_prefill(names, reps: int = 5):
             row[label + "_ms_per_ring"] = round(sec * 1e3, 3)
             row[label + "_us_per_call"] = round(sec * 1e6 / (n * n), 2)
             row[label + "_tflops"] = round(flop / sec / 1e12, 1)
+        # pass-Q with the (small) query shards gathered: one call per KV holder answers all
+        # 16 steps, then the same 16 merges
+        m = len(qpos[0])
+        q_all = take(q, np.concatenate(qpos) - p_cached)
+        qpos_all = _i32(np.concatenate(qpos))
+        gring = B.Ring([q_all[r * m:(r + 1) * m] for r in range(n)], ring.tensors[1],
+                       ring.tensors[2], [qpos_all[r * m:(r + 1) * m] for r in range(n)],
+                       ring.tensors[4], out_dtype=torch.bfloat16, keep_partials=True,
+                       gathered_q=True)
+        sec = time_steps(lambda: B.cp_ring_passq(gring), reps, 2)
+        row["passq_gathered_ms_per_ring"] = round(sec * 1e3, 3)
+        row["passq_gathered_us_per_rank"] = round(sec * 1e6 / n, 2)
+        row["passq_gathered_tflops"] = round(flop / sec / 1e12, 1)
+        row["passq_gathered_max_abs_diff"] = round(max(
+            float((a.float() - b.float()).abs().max()) for a, b in zip(gring.out, ring.out)), 5)
+        del gring
         rows.append(row)
         del ring, q, k, v
         torch.cuda.empty_cache()

@@ -287,6 +287,17 @@ typedef struct {
   const int32_t* const* arrived;
   int32_t* ring_error;
   int32_t spin_limit;
+  /*
+   * Pass-Q drivers only. 1: the query shards of all ranks lie back to back in one buffer
+   * (q[s + 1] == q[s] + n_q[s] rows, the same for q_pos and, for decode, bid; all n_q equal
+   * and nonzero) - the small Q all-gathered instead of passed round the ring - and every KV
+   * holder k answers all N steps with ONE call over the gathered queries. Requires
+   * keep_partials (n_ranks * n_ranks slots), in which the partial of the queries of rank a
+   * against the KV of rank b is then in slot b * n_ranks + a: the N slots a holder writes
+   * are contiguous, its All2All send buffer in destination order. Not with message_layout
+   * or fused_merge; CP_ERR_UNSUPPORTED if the shards are not laid out as described. 0: off.
+   */
+  int32_t gathered_q;
 } cp_ring_desc;
 
 /* Bytes of one message of message_layout 1 (see cp_ring_desc); 0 for an invalid descriptor.

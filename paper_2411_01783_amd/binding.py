@@ -56,7 +56,8 @@ class cp_ring_desc(ctypes.Structure):
                 ("batch", _i32),
                 ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp)),
                 ("aux_stream", _vp), ("message_layout", _i32),
-                ("arrived", ctypes.POINTER(_vp)), ("ring_error", _vp), ("spin_limit", _i32)]
+                ("arrived", ctypes.POINTER(_vp)), ("ring_error", _vp), ("spin_limit", _i32),
+                ("gathered_q", _i32)]
 
 
 class cp_select_params(ctypes.Structure):
@@ -393,7 +394,8 @@ class Ring:
                  cu_seqlens_kv: Optional[List[torch.Tensor]] = None,
                  bid: Optional[List[torch.Tensor]] = None, aux_stream=None,
                  fused_merge=False, message_layout: bool = False,
-                 arrived: Optional[List[torch.Tensor]] = None, spin_limit: int = 1 << 20):
+                 arrived: Optional[List[torch.Tensor]] = None, spin_limit: int = 1 << 20,
+                 gathered_q: bool = False):
         n = len(q)
         self.n = n
         self.decode = cu_seqlens_kv is not None
@@ -404,8 +406,16 @@ class Ring:
         self.tensors = (q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid)  # keep alive
         self.n_q = [int(t.shape[0]) for t in q]
         self.n_kv = [int(t.shape[0]) for t in k]
-        self.out = [torch.empty((m, nh, d), dtype=odt, device=dev) for m in self.n_q]
-        self.lse = [torch.empty((m, nh), dtype=torch.float32, device=dev) for m in self.n_q]
+        if gathered_q:   # outputs back to back like the queries: one merge launch for all ranks
+            tot = sum(self.n_q)
+            self.out_all = torch.empty((tot, nh, d), dtype=odt, device=dev)
+            self.lse_all = torch.empty((tot, nh), dtype=torch.float32, device=dev)
+            ends = np.cumsum([0] + self.n_q)
+            self.out = [self.out_all[ends[i]:ends[i + 1]] for i in range(n)]
+            self.lse = [self.lse_all[ends[i]:ends[i + 1]] for i in range(n)]
+        else:
+            self.out = [torch.empty((m, nh, d), dtype=odt, device=dev) for m in self.n_q]
+            self.lse = [torch.empty((m, nh), dtype=torch.float32, device=dev) for m in self.n_q]
         max_q = max(self.n_q) if self.n_q else 0
         slots = n * n if keep_partials else (1 if fused_merge else n)
         self.keep = keep_partials
@@ -442,6 +452,8 @@ class Ring:
             dsc.partial_out, dsc.partial_lse = _ptr(self.partial_out), _ptr(self.partial_lse)
         dsc.keep_partials = 1 if keep_partials else 0
         dsc.fused_merge = int(fused_merge)   # False/True, or 2: all steps of a rank in one launch
+        dsc.gathered_q = 1 if gathered_q else 0
+        self.gathered = gathered_q
         self.arrived = arrived
         if arrived is not None:
             self._arrived = (_vp * n)(*[_ptr(t) for t in arrived])
@@ -468,7 +480,8 @@ class Ring:
         """Partial (O, LSE) of rank a's queries against rank b's KV (keep_partials only)."""
         assert self.keep
         m = self.n_q[a]
-        return self.partial_out[a * self.n + b, :m], self.partial_lse[a * self.n + b, :m]
+        slot = b * self.n + a if self.gathered else a * self.n + b
+        return self.partial_out[slot, :m], self.partial_lse[slot, :m]
 
 
 def cp_ring_passkv(ring: Ring, stream=None):

@@ -222,6 +222,9 @@ static int check_ring(const cp_ring_desc* d, bool decode) {
   if (d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS) return CP_ERR_SHAPE;
   if (d->fused_merge < 0 || d->fused_merge > 2) return CP_ERR_SHAPE;
   if (d->message_layout != 0 && d->message_layout != 1) return CP_ERR_SHAPE;
+  if (d->gathered_q != 0 && d->gathered_q != 1) return CP_ERR_SHAPE;
+  if (d->gathered_q && (!d->keep_partials || d->message_layout || d->fused_merge))
+    return CP_ERR_UNSUPPORTED;
   if (d->fused_merge && (decode || d->keep_partials || d->part_dtype != CP_FP32))
     return CP_ERR_UNSUPPORTED;
   if (d->n_q == nullptr || d->n_kv == nullptr || d->q == nullptr || d->k == nullptr ||
@@ -287,6 +290,14 @@ extern "C" size_t cp_ring_workspace_bytes(const cp_ring_desc* d, int32_t decode)
       cp_shape s = ring_shape(d, a, b, decode != 0);
       need = std::max(need, cp_workspace_bytes(&s, decode ? CP_WS_DECODE : CP_WS_PARTIAL));
     }
+  if (d->gathered_q) {
+    for (int b = 0; b < d->n_ranks; ++b) {
+      cp_shape s = ring_shape(d, 0, b, decode != 0);
+      s.total_q = 0;
+      for (int a = 0; a < d->n_ranks; ++a) s.total_q += d->n_q[a];
+      need = std::max(need, cp_workspace_bytes(&s, decode ? CP_WS_DECODE : CP_WS_PARTIAL));
+    }
+  }
   return need + ring_bounds_bytes(d, decode != 0);
 }
 
@@ -508,6 +519,7 @@ size_t cp_ring_message_bytes(const cp_ring_desc* d) {
 int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
   int rc = check_ring(d, false);
   if (rc != CP_OK) return rc;
+  if (d->gathered_q) return CP_ERR_UNSUPPORTED;  // pass-Q only
   hipStream_t st = (hipStream_t)stream;
   const RingSlots slots = make_slots(d);
   const int n = d->n_ranks;
@@ -535,10 +547,94 @@ int cp_ring_passkv(const cp_ring_desc* d, void* stream) {
   return rc;
 }
 
+// gathered_q: the query shards of all source ranks lie back to back in one buffer (an
+// all-gather of the small Q instead of passing it round), so a KV holder answers all N ring
+// steps of Algorithms 3 / 4 with one call over the gathered queries. Its output block, N slots
+// of equal size, is the holder's All2All send buffer in destination order.
+static bool queries_are_gathered(const cp_ring_desc* d, bool decode) {
+  const size_t row = (size_t)d->n_q_heads * d->head_dim * elem_size(d->dtype);
+  for (int s = 0; s < d->n_ranks; ++s) {
+    if (d->n_q[s] != d->n_q[0] || d->n_q[s] == 0) return false;
+    if (s == 0) continue;
+    if ((const char*)d->q[s] != (const char*)d->q[s - 1] + d->n_q[s - 1] * row) return false;
+    if (d->q_pos[s] != d->q_pos[s - 1] + d->n_q[s - 1]) return false;
+    if (decode && d->bid[s] != d->bid[s - 1] + d->n_q[s - 1]) return false;
+  }
+  return true;
+}
+
+static int ring_passq_gathered(const cp_ring_desc* d, bool decode, hipStream_t st) {
+  if (!queries_are_gathered(d, decode)) return CP_ERR_UNSUPPORTED;
+  const RingSlots slots = make_slots(d);
+  const int n = d->n_ranks;
+  RingWork w;
+  int rc = ring_prepare(d, decode, st, w);
+  if (rc != CP_OK) return rc;
+  for (int k = 0; k < n && rc == CP_OK; ++k) {
+    cp_shape s = ring_shape(d, 0, k, decode);
+    s.total_q = (int64_t)n * d->n_q[0];
+    void* const o = slots.out((int64_t)k * n);
+    float* const l = slots.lse((int64_t)k * n);
+    if (decode) {
+      rc = cp_attn_decode(&s, d->q[0], d->k[k], d->v[k], d->q_pos[0], d->kv_pos[k],
+                          d->cu_seqlens_kv[k], d->bid[0], o, l, d->part_dtype, w.call_ws,
+                          w.call_ws_bytes, st);
+    } else if (w.use_bounds) {
+      if (!aligned16(d->q[0]) || !aligned16(d->k[k]) || !aligned16(d->v[k])) rc = CP_ERR_ALIGN;
+      else
+        rc = launch_prefill_mfma(s, resolve_scale(s.softmax_scale, s.head_dim), d->q[0], d->k[k],
+                                 d->v[k], d->q_pos[0], d->kv_pos[k], o, l, d->part_dtype,
+                                 w.call_ws, w.call_ws_bytes,
+                                 (char*)d->workspace + w.bounds_off[k], nullptr, st, nullptr);
+    } else {
+      rc = cp_attn_partial(&s, d->q[0], d->k[k], d->v[k], d->q_pos[0], d->kv_pos[k], nullptr,
+                           nullptr, o, l, d->part_dtype, w.call_ws, w.call_ws_bytes, st);
+    }
+  }
+  // The All2All: source rank a merges slot k * n + a of every holder k. When the outputs of
+  // the ranks lie back to back as the queries do, the N merges are one launch over the
+  // holders' whole blocks.
+  const size_t out_row = (size_t)d->n_q_heads * d->head_dim * elem_size(d->out_dtype);
+  bool one_merge = slots.max_q == d->n_q[0];
+  for (int a = 1; a < n && one_merge; ++a) {
+    one_merge = (char*)d->out[a] == (char*)d->out[a - 1] + d->n_q[a - 1] * out_row;
+    if (d->lse != nullptr)
+      one_merge = one_merge && d->lse[a] != nullptr &&
+                  d->lse[a] == d->lse[a - 1] + d->n_q[a - 1] * d->n_q_heads;
+  }
+  if (one_merge && (d->lse == nullptr || d->lse[0] != nullptr) && rc == CP_OK) {
+    const void* outs[CP_MAX_PARTS];
+    const float* lses[CP_MAX_PARTS];
+    for (int k = 0; k < n; ++k) {
+      outs[k] = slots.out((int64_t)k * n);
+      lses[k] = slots.lse((int64_t)k * n);
+    }
+    rc = cp_attn_merge((int64_t)n * d->n_q[0] * d->n_q_heads, d->head_dim, n, outs, lses,
+                       d->part_dtype, d->out[0], d->out_dtype,
+                       d->lse != nullptr ? d->lse[0] : nullptr, st);
+    ring_finish(w);
+    return rc;
+  }
+  for (int a = 0; a < n && rc == CP_OK; ++a) {
+    const void* outs[CP_MAX_PARTS];
+    const float* lses[CP_MAX_PARTS];
+    for (int k = 0; k < n; ++k) {
+      outs[k] = slots.out((int64_t)k * n + a);
+      lses[k] = slots.lse((int64_t)k * n + a);
+    }
+    float* lse_out = d->lse != nullptr ? d->lse[a] : nullptr;
+    rc = cp_attn_merge(d->n_q[a] * d->n_q_heads, d->head_dim, n, outs, lses, d->part_dtype,
+                       d->out[a], d->out_dtype, lse_out, st);
+  }
+  ring_finish(w);
+  return rc;
+}
+
 static int ring_passq_common(const cp_ring_desc* d, bool decode, void* stream) {
   int rc = check_ring(d, decode);
   if (rc != CP_OK) return rc;
   if (d->fused_merge == 2) return CP_ERR_UNSUPPORTED;  // pass-KV only: the queries stay put
+  if (d->gathered_q) return ring_passq_gathered(d, decode, (hipStream_t)stream);
   hipStream_t st = (hipStream_t)stream;
   const RingSlots slots = make_slots(d);
   const int n = d->n_ranks;

@@ -649,3 +649,82 @@ def test_hbm_read_probe_reads_every_chunk_once(n_words, n_wg):
     # the xor of what the threads folded is the xor of the buffer iff no chunk was skipped or
     # read twice (random words: a chunk read twice cancels, a skipped one is missing)
     assert np.bitwise_xor.reduce(sink.cpu().numpy()) == np.bitwise_xor.reduce(host)
+
+
+# ---------------------------------------------------------------------------
+# pass-Q with gathered queries: one call per KV holder answers all N ring steps
+# ---------------------------------------------------------------------------
+
+def test_ring_passq_gathered_queries_partial_prefill(oracle):
+    n, p_cached, t_new, nh, d = 4, 3000, 256, 16, 128
+    q, q64 = randn(131, (t_new, nh, d))
+    k, k64 = randn(132, (p_cached + t_new, 1, d))
+    v, v64 = randn(133, (p_cached + t_new, 1, d))
+    sh = oracle.shard_partial_prefill(p_cached, t_new, n)
+    m = len(sh[0][0])
+    assert all(len(qp) == m for qp, _ in sh)
+    ref_o, ref_l, part_o, part_l = oracle.ring_passq(
+        [q64[qp - p_cached] for qp, _ in sh], [k64[kp] for _, kp in sh],
+        [v64[kp] for _, kp in sh], [qp for qp, _ in sh], [kp for _, kp in sh])
+    # the gathered buffers: shards back to back in rank order
+    order = np.concatenate([qp for qp, _ in sh])
+    q_all, qpos_all = dev(q[order - p_cached]), i32(order)
+    qs = [q_all[s * m:(s + 1) * m] for s in range(n)]
+    qps = [qpos_all[s * m:(s + 1) * m] for s in range(n)]
+    kv = ([dev(k[kp]) for _, kp in sh], [dev(v[kp]) for _, kp in sh])
+    ring = B.Ring(qs, kv[0], kv[1], qps, [i32(kp) for _, kp in sh], out_dtype=torch.float32,
+                  keep_partials=True, gathered_q=True)
+    out, lse = B.cp_ring_passq(ring)
+    torch.cuda.synchronize()
+    for s in range(n):
+        check(out[s], lse[s], ref_o[s], ref_l[s], what="merged, source %d" % s)
+        for kk in range(n):
+            po, pl = ring.partial(s, kk)
+            check(po, pl, part_o[s][kk], part_l[s][kk], what="partial %d vs KV %d" % (s, kk))
+    # a holder's N partials are one contiguous block in destination order (its send buffer)
+    assert ring.partial_out[2 * n:3 * n].is_contiguous()
+    po, _ = ring.partial(1, 2)
+    assert po.data_ptr() == ring.partial_out[2 * n + 1].data_ptr()
+    # shards that are not back to back are refused, and so is the pass-KV driver
+    swapped = [qs[1], qs[0]] + qs[2:]
+    loose = B.Ring(swapped, kv[0], kv[1], qps, [i32(kp) for _, kp in sh],
+                   out_dtype=torch.float32, keep_partials=True, gathered_q=True)
+    with pytest.raises(B.CpError):
+        B.cp_ring_passq(loose)
+    with pytest.raises(B.CpError):
+        B.cp_ring_passkv(ring)
+
+
+def test_ring_passq_gathered_queries_decode(oracle):
+    n, nh = 4, 16
+    lengths = [900, 35, 2300, 1, 640, 1200, 77, 3000]
+    ks = [W.normal(200 + b, (L, 1, 128)) for b, L in enumerate(lengths)]
+    vs = [W.normal(300 + b, (L, 1, 128)) for b, L in enumerate(lengths)]
+    qs = [W.normal(400 + b, (1, nh, 128)) for b in range(len(lengths))]
+    ranks = oracle.shard_decode_batch(lengths, n, decode_iter=3)
+
+    def gather(src, r):
+        if len(r["kv_pos"]) == 0:
+            return torch.zeros((0, 1, 128), dtype=torch.bfloat16)
+        return torch.cat([src[b][p][None] for b, p in zip(r["kv_seq"], r["kv_pos"])])
+    rk = [gather(ks, r) for r in ranks]
+    rv = [gather(vs, r) for r in ranks]
+    rq = [torch.cat([qs[b] for b in r["bid"]]) for r in ranks]
+    ref_o, ref_l, _, _ = oracle.ring_passq_decode(
+        [W.to_f64(x) for x in rq], [r["bid"] for r in ranks], [r["q_pos"] for r in ranks],
+        [W.to_f64(x) for x in rk], [W.to_f64(x) for x in rv], [r["kv_pos"] for r in ranks],
+        [r["cu_kv"] for r in ranks])
+    m = len(ranks[0]["bid"])
+    assert all(len(r["bid"]) == m for r in ranks)
+    q_all = dev(torch.cat(rq))
+    qpos_all = i32(np.concatenate([r["q_pos"] for r in ranks]))
+    bid_all = i32(np.concatenate([r["bid"] for r in ranks]))
+    sl = [slice(s * m, (s + 1) * m) for s in range(n)]
+    ring = B.Ring([q_all[x] for x in sl], [dev(x) for x in rk], [dev(x) for x in rv],
+                  [qpos_all[x] for x in sl], [i32(r["kv_pos"]) for r in ranks],
+                  out_dtype=torch.float32, keep_partials=True, gathered_q=True,
+                  cu_seqlens_kv=[i32(r["cu_kv"]) for r in ranks], bid=[bid_all[x] for x in sl])
+    out, lse = B.cp_ring_passq_decode(ring)
+    torch.cuda.synchronize()
+    for s in range(n):
+        check(out[s], lse[s], ref_o[s], ref_l[s], what="gathered decode, source %d" % s)
