@@ -105,9 +105,11 @@ def test_prefill_1m_one_rank_sampled(oracle):
     assert rel_l2(out[sel], ref_o) < 2e-2
 
 
+@pytest.mark.parametrize("gathered", [False, True])
 @pytest.mark.parametrize("name", ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
                                   "partial_prefill_128k_t8192"])
-def test_partial_prefill_passq_ring_sampled(oracle, name):
+def test_partial_prefill_passq_ring_sampled(oracle, name, gathered):
+    # gathered: the 16 query shards back to back, one call per KV holder for all 16 steps
     w = W.WORKLOADS[name]
     q, k, v = W.qkv(w, device="cuda")
     n, p_cached, t_new = w.n_ranks, w.p_cached, w.t_new
@@ -119,9 +121,16 @@ def test_partial_prefill_passq_ring_sampled(oracle, name):
 
     def take(t, p):
         return t[torch.as_tensor(p.astype(np.int64)).to("cuda")].contiguous()
-    ring = B.Ring([take(q, p - p_cached) for p in qpos], [take(k, p) for p in kvpos],
-                  [take(v, p) for p in kvpos], [i32(p) for p in qpos], [i32(p) for p in kvpos],
-                  out_dtype=torch.bfloat16)
+    if gathered:
+        m = len(qpos[0])
+        q_all, qpos_all = take(q, np.concatenate(qpos) - p_cached), i32(np.concatenate(qpos))
+        qs = [q_all[r * m:(r + 1) * m] for r in range(n)]
+        qps = [qpos_all[r * m:(r + 1) * m] for r in range(n)]
+    else:
+        qs, qps = [take(q, p - p_cached) for p in qpos], [i32(p) for p in qpos]
+    ring = B.Ring(qs, [take(k, p) for p in kvpos], [take(v, p) for p in kvpos], qps,
+                  [i32(p) for p in kvpos], out_dtype=torch.bfloat16, keep_partials=gathered,
+                  gathered_q=gathered)
     out, lse = B.cp_ring_passq(ring)
     torch.cuda.synchronize()
     k64, v64 = W.to_f64(k), W.to_f64(v)
@@ -165,6 +174,21 @@ def test_decode_b32_passq_ring_full(oracle):
     ring = B.Ring(rq, rk, rv, rqpos, rpos, out_dtype=torch.float32, cu_seqlens_kv=rcu, bid=rbid)
     out, lse = B.cp_ring_passq_decode(ring)
     torch.cuda.synchronize()
+    # the same with the queries gathered: one decode call per KV holder for all 32 queries,
+    # one merge across the holders
+    per = w.batch // n
+    q_g, qpos_g, bid_g = torch.cat(rq), torch.cat(rqpos), torch.cat(rbid)
+    sl = [slice(r * per, (r + 1) * per) for r in range(n)]
+    gring = B.Ring([q_g[x] for x in sl], rk, rv, [qpos_g[x] for x in sl], rpos,
+                   out_dtype=torch.float32, keep_partials=True, gathered_q=True,
+                   cu_seqlens_kv=rcu, bid=[bid_g[x] for x in sl])
+    gout, glse = B.cp_ring_passq_decode(gring)
+    torch.cuda.synchronize()
+    for r in range(n):
+        # (different split counts for 2 and for 32 queries: same result up to fp32 rounding;
+        # the step-by-step outputs are compared with the oracle below)
+        assert float((gout[r] - out[r]).abs().max()) < 1e-4
+        assert float((glse[r] - lse[r]).abs().max()) < 1e-4
     for r in range(n):
         for i, b in enumerate(rbid[r].cpu().numpy()):
             L = int(lengths[b])
