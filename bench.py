@@ -197,7 +197,7 @@ def build_decode(w: W.Workload):
     return dict(ranks=ranks, q=q, q_pos=q_pos, bid=bid, lengths=lengths)
 
 
-def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False):
+def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False, ring: bool = True):
     st = build_decode(w)
     n = w.n_ranks
     shape = B.make_shape(B.CP_BF16, w.head_dim, w.n_q_heads, w.n_kv_heads, w.batch,
@@ -220,6 +220,8 @@ def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False):
                kv_mb_per_rank=kv_bytes / n / 1e6)
     # All of Algorithm 4 through the driver, queries gathered: 16 decode calls (one per KV
     # holder, all 32 queries) and the merge across holders of every query's 16 partials
+    if not ring:
+        return res
     order = np.argsort(np.arange(w.batch) % n, kind="stable")   # rank r owns b with b % n == r
     per = w.batch // n
     q_g, qpos_g, bid_g = st["q"][order].contiguous(), st["q_pos"][order].contiguous(), _i32(order)
@@ -430,7 +432,7 @@ def pmc_probe(st):
     torch.cuda.synchronize()
     B.cp_ring_passkv(st["parts"])
     torch.cuda.synchronize()
-    bench_decode(W.WORKLOADS["decode_b32"], reps=1)
+    bench_decode(W.WORKLOADS["decode_b32"], reps=1, ring=False)
     print("pmc probe done")
 
 
