@@ -235,8 +235,8 @@ typedef struct {
    * 2 (cp_ring_passkv only): one launch per rank walks the KV shards of all N ring steps in
    * ring order with one running softmax state in registers, so Equation 4 is applied inside
    * the online softmax and only the rank's output is written: no partials, no merge pass, no
-   * per-step launch. Same requirements as 1, and in addition all n_kv[k] equal and a multiple
-   * of 128 and n_ranks <= 32. See `arrived` below for how a step waits for its shard.
+   * per-step launch. Same requirements as 1 (decided on the largest KV shard), and
+   * n_ranks <= 32. See `arrived` below for how a step waits for its shard.
    */
   int32_t fused_merge;
   void* workspace; /* (device) max over ranks of the per-call workspace */

@@ -420,20 +420,23 @@ int ring_rank_walk(const cp_ring_desc* d, const RingWork& w, const RingSlots& sl
   const void* v[CP_MAX_PARTS];
   const int32_t* pos[CP_MAX_PARTS];
   const void* bounds[CP_MAX_PARTS];
+  int64_t n_kv[CP_MAX_PARTS];
+  int64_t largest = 0;
   for (int j = 0; j < n; ++j) {
     const int s = kv_of_step(j);
-    if (d->n_kv[s] != d->n_kv[0]) return CP_ERR_UNSUPPORTED;  // equal shards only
     if (!aligned16(d->k[s]) || !aligned16(d->v[s])) return CP_ERR_ALIGN;
-    k[j] = d->k[s]; v[j] = d->v[s]; pos[j] = d->kv_pos[s];
+    k[j] = d->k[s]; v[j] = d->v[s]; pos[j] = d->kv_pos[s]; n_kv[j] = d->n_kv[s];
     bounds[j] = (const char*)d->workspace + w.bounds_off[s];
+    largest = std::max(largest, d->n_kv[s]);
   }
   if (!aligned16(d->q[a])) return CP_ERR_ALIGN;
-  const cp_shape s = ring_shape(d, a, 0, false);
+  cp_shape s = ring_shape(d, a, 0, false);
+  s.total_kv = largest;
   if (!prefill_ring_walk_applies(s, n)) return CP_ERR_UNSUPPORTED;
   const int32_t* arrived = d->arrived != nullptr ? d->arrived[a] : nullptr;
   float* const lse_out = d->lse != nullptr ? d->lse[a] : nullptr;
   return launch_prefill_mfma_ring(s, resolve_scale(s.softmax_scale, s.head_dim), d->q[a],
-                                  d->q_pos[a], n, k, v, pos, bounds, arrived, d->ring_error,
+                                  d->q_pos[a], n, k, v, pos, bounds, n_kv, arrived, d->ring_error,
                                   d->spin_limit, d->out[a],
                                   lse_out != nullptr ? lse_out : slots.lse(0),  // LSE not wanted
                                   d->out_dtype, st);

@@ -67,9 +67,11 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
                         const void* tile_bounds, const int32_t* q_lo, hipStream_t stream,
                         const PrefillAccumulate* acc = nullptr);
 
-// One launch for all ring steps of a rank (pass-KV): the shards k[j], v[j], kv_pos[j] (each
-// s.total_kv tokens, a multiple of 128) with their tile bounds, in ring order j = 0..n_shards-1,
-// walked by every workgroup with one running softmax state; writes the rank's merged O / LSE.
+// One launch for all ring steps of a rank (pass-KV): the shards k[j], v[j], kv_pos[j] (n_kv[j]
+// tokens each; any sizes, empty ones included) with their tile bounds, in ring order
+// j = 0..n_shards-1, walked by every workgroup with one running softmax state; writes the
+// rank's merged O / LSE. s.total_kv is the largest shard (it decides, with total_q, whether
+// the launch would split its KV axis, which the walk does not support).
 // `arrived` (device, or NULL): int32 per step, the kernel waits (at most spin_limit polls) for
 // a nonzero value before it reads step j's shard; a wait that gives up sets *error = 1 and
 // leaves the shard out.
@@ -77,8 +79,9 @@ bool prefill_ring_walk_applies(const cp_shape& s, int n_shards);
 int launch_prefill_mfma_ring(const cp_shape& s, float scale, const void* q, const int32_t* q_pos,
                              int n_shards, const void* const* k, const void* const* v,
                              const int32_t* const* kv_pos, const void* const* bounds,
-                             const int32_t* arrived, int32_t* error, int32_t spin_limit, void* out,
-                             float* lse, int32_t out_dtype, hipStream_t stream);
+                             const int64_t* n_kv, const int32_t* arrived, int32_t* error,
+                             int32_t spin_limit, void* out, float* lse, int32_t out_dtype,
+                             hipStream_t stream);
 
 // Packed batches on the MFMA path: per-sequence position ranges (see cp_varseq.hip).
 struct VarseqLayout {

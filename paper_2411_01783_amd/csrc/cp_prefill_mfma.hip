@@ -83,6 +83,8 @@ struct RingShard {
   const bf16_t* v;
   const int32_t* kv_pos;
   const int2* bounds;  // (min, max) of kv_pos per tile of this shard
+  int32_t total_kv;    // tokens in this shard
+  int32_t n_tiles;     // ceil(total_kv / TILE)
 };
 struct RingTable {
   RingShard shard[kMaxRingShards];
@@ -258,7 +260,6 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
 
 bool prefill_ring_walk_applies(const cp_shape& s, int n_shards) {
   if (n_shards < 1 || n_shards > kMaxRingShards) return false;
-  if (s.total_kv <= 0 || s.total_kv % TILE != 0) return false;
   const Plan pl = make_plan(s);
   return pl.n_row_blocks > 0 && pl.n_splits == 1;
 }
@@ -266,8 +267,9 @@ bool prefill_ring_walk_applies(const cp_shape& s, int n_shards) {
 int launch_prefill_mfma_ring(const cp_shape& s, float scale, const void* q, const int32_t* q_pos,
                              int n_shards, const void* const* k, const void* const* v,
                              const int32_t* const* kv_pos, const void* const* bounds,
-                             const int32_t* arrived, int32_t* error, int32_t spin_limit, void* out,
-                             float* lse, int32_t out_dtype, hipStream_t stream) {
+                             const int64_t* n_kv, const int32_t* arrived, int32_t* error,
+                             int32_t spin_limit, void* out, float* lse, int32_t out_dtype,
+                             hipStream_t stream) {
   if (!prefill_ring_walk_applies(s, n_shards)) return CP_ERR_UNSUPPORTED;
   if (arrived != nullptr && (error == nullptr || spin_limit < 1)) return CP_ERR_SHAPE;
   if (s.n_kv_heads > 65535) return CP_ERR_SHAPE;
@@ -289,8 +291,12 @@ int launch_prefill_mfma_ring(const cp_shape& s, float scale, const void* q, cons
   p.scale_log2 = scale * kLog2e;
   RingTable rt = {};
   for (int j = 0; j < n_shards; ++j) {
-    if (k[j] == nullptr || v[j] == nullptr || kv_pos[j] == nullptr || bounds[j] == nullptr)
+    if (n_kv[j] < 0 || n_kv[j] > INT32_MAX - TILE) return CP_ERR_SHAPE;
+    if (n_kv[j] > 0 &&
+        (k[j] == nullptr || v[j] == nullptr || kv_pos[j] == nullptr || bounds[j] == nullptr))
       return CP_ERR_NULL;
+    rt.shard[j].total_kv = (int32_t)n_kv[j];
+    rt.shard[j].n_tiles = (int32_t)((n_kv[j] + TILE - 1) / TILE);
     rt.shard[j].k = (const bf16_t*)k[j];
     rt.shard[j].v = (const bf16_t*)v[j];
     rt.shard[j].kv_pos = kv_pos[j];

@@ -329,8 +329,11 @@ __device__ __forceinline__ int ring_flag(const RingTable& ring, int step) {
 __device__ __forceinline__ bool ring_enter(const RingTable& ring, int shard, int kvh, int tid,
                                            int* wg_scratch, int& peek, const char*& k_head,
                                            const char*& v_head, const int32_t*& kv_pos_cur,
-                                           const int2*& bounds_cur) {
+                                           const int2*& bounds_cur, int32_t& total_kv,
+                                           int& t_end) {
   const RingShard& e = ring.shard[shard];
+  total_kv = e.total_kv;
+  t_end = e.n_tiles;
   k_head = (const char*)e.k + (int64_t)kvh * ROW_BYTES;
   v_head = (const char*)e.v + (int64_t)kvh * ROW_BYTES;
   kv_pos_cur = e.kv_pos;
@@ -365,14 +368,15 @@ __device__ __forceinline__ bool ring_enter(const RingTable& ring, int shard, int
   return ok != 0;
 }
 __device__ __forceinline__ bool ring_enter(const NoRing&, int, int, int, int*, int&, const char*&,
-                                           const char*&, const int32_t*&, const int2*&) {
+                                           const char*&, const int32_t*&, const int2*&, int32_t&,
+                                           int&) {
   return true;
 }
 
 // RING: one launch walks the KV shards of all ring steps of a rank, in ring order, with one
 // running (O, l, m) in registers: the merge of Equation 4 happens inside the online softmax
-// and nothing but the rank's final output is written. `ring` names the shards (same size each,
-// a multiple of TILE) and, optionally, one arrival flag per step that the workgroup waits for
+// and nothing but the rank's final output is written. `ring` names the shards (any sizes, empty
+// ones included) and, optionally, one arrival flag per step that the workgroup waits for
 // (bounded) before it touches the shard.
 template <typename TO, bool BAND, bool SPLIT, bool ACC, bool RING>
 __device__ __forceinline__ void prefill_body(const Params& p,
@@ -407,13 +411,17 @@ __device__ __forceinline__ void prefill_body(const Params& p,
   const int64_t row_lin = (token * p.n_kv_heads + kvh) * p.group + hg;  // index into [tokens, N_H]
   const int32_t qp = row_ok ? p.q_pos[token] : CP_POS_PAD_Q;
   const int32_t ql = BAND && row_ok ? p.q_lo[token] : INT32_MIN;
-  const int32_t total_kv = p.total_kv;
+  int32_t total_kv = p.total_kv;  // (the ring walk sets it, and t_end, per shard)
   const float scale_log2 = p.scale_log2;
   // The start-up chain is q_pos -> visible tiles -> first tile; the bounds of the first 512
   // tiles are requested now so that they arrive together with q_pos, and the Q fragments
   // (needed last) are requested after both and waited for only before the first product.
   const int t_begin = split * p.tiles_per_split;
-  const int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
+  int t_end = min(p.n_tiles, t_begin + p.tiles_per_split);
+  if constexpr (RING) {
+    total_kv = ring.shard[0].total_kv;
+    t_end = ring.shard[0].n_tiles;
+  }
   int2 first_bounds = make_int2(0, 0);
   const int2* bounds_cur = tile_bounds;
   if constexpr (RING) bounds_cur = ring.shard[0].bounds;
@@ -527,7 +535,7 @@ __device__ __forceinline__ void prefill_body(const Params& p,
   for (int shard = 0; shard < n_shards; ++shard) {
     if constexpr (RING) {
       if (!ring_enter(ring, shard, kvh, tid, wg_scratch, flag_peek, k_head, v_head, kv_pos_cur,
-                      bounds_cur))
+                      bounds_cur, total_kv, t_end))
         continue;  // the shard never arrived: reported through ring.error, walk goes on
     }
     for (int c0 = t_begin; c0 < t_end; c0 += MAX_LIVE) {
