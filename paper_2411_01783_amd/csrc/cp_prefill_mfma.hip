@@ -26,6 +26,11 @@
 //     (grid.z); split results go to the workspace and are combined with Eq. 4.
 //   - The epilogue transposes the accumulators through LDS so that every output
 //     row leaves as one contiguous 512-byte (fp32) or 256-byte (bf16) run.
+//   - Across ring steps the same body runs three ways: a launch per step into a stored
+//     partial; a launch per step that merges into a running (O, LSE) in its epilogue
+//     (ACC); or one launch per rank that walks the shards of all ring steps in ring
+//     order, each behind an arrival flag, keeping the running softmax state in
+//     registers (RING, prefill_ring_walk_kernel).
 #include <type_traits>
 
 #include "cp_common.h"
