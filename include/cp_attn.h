@@ -241,7 +241,7 @@ typedef struct {
   int32_t fused_merge;
   void* workspace; /* (device) max over ranks of the per-call workspace */
   size_t workspace_bytes;
-  /* decode only (cp_ring_passq_decode); NULL otherwise */
+  /* decode (cp_ring_passq_decode) and packed prefill batches (cu_seqlens_q below) */
   int32_t batch;                       /* sequences packed in every rank's KV */
   const int32_t* const* cu_seqlens_kv; /* (host) -> (device) int32 [batch+1] per rank */
   const int32_t* const* bid;           /* (host) -> (device) int32 [n_q[k]] per rank */
@@ -298,6 +298,17 @@ typedef struct {
    * or fused_merge; CP_ERR_UNSUPPORTED if the shards are not laid out as described. 0: off.
    */
   int32_t gathered_q;
+  /*
+   * Prefill drivers over packed batches (the fused variable-length inputs of Algorithm 2,
+   * Section 3.4), or NULL for one sequence. Not NULL: every rank's Q holds `batch` sequences
+   * back to back, its share of each, with cu_seqlens_q[k] (device int32 [batch+1]) as the
+   * boundaries, and its KV likewise with cu_seqlens_kv[k]; a query sees the keys of its own
+   * sequence only. Each rank's share of a sequence follows the same sharding rule, so a
+   * sequence shorter than 2N tokens leaves some ranks an empty segment; equal-size messages
+   * are the caller's padding (CP_POS_PAD_KV / CP_POS_PAD_Q). Plain drivers only: not with
+   * fused_merge, gathered_q or aux_stream.
+   */
+  const int32_t* const* cu_seqlens_q;
 } cp_ring_desc;
 
 /* Bytes of one message of message_layout 1 (see cp_ring_desc); 0 for an invalid descriptor.

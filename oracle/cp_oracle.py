@@ -313,8 +313,10 @@ class KVCache:
 # Algorithms 2, 3, 4: the ring, simulated over virtual ranks
 # --------------------------------------------------------------------------
 
-def ring_passkv(q, k, v, q_pos, kv_pos, scale: Optional[float] = None):
-    """Algorithm 2. Arguments are per-rank lists (length N).
+def ring_passkv(q, k, v, q_pos, kv_pos, scale: Optional[float] = None, cu_q=None, cu_kv=None):
+    """Algorithm 2. Arguments are per-rank lists (length N). With cu_q / cu_kv (per-rank
+    sequence boundaries) every rank's Q and KV are a packed batch, the fused variable-length
+    input of the algorithm: a query sees the keys of its own sequence only.
 
     Every rank starts holding its own KV shard; at step j rank k holds the
     shard that started on rank s = (k - j) mod N, attends its queries to it,
@@ -332,6 +334,8 @@ def ring_passkv(q, k, v, q_pos, kv_pos, scale: Optional[float] = None):
             s = (kk - j) % n
             assert held[kk] == s
             part_o[kk][s], part_l[kk][s] = attn(q[kk], k[s], v[s], q_pos[kk], kv_pos[s],
+                                                cu_q=None if cu_q is None else cu_q[kk],
+                                                cu_kv=None if cu_kv is None else cu_kv[s],
                                                 scale=scale)
         held = [held[(kk - 1) % n] for kk in range(n)]  # receive from previous rank
     out, lse = [], []
@@ -342,8 +346,8 @@ def ring_passkv(q, k, v, q_pos, kv_pos, scale: Optional[float] = None):
     return out, lse, part_o, part_l
 
 
-def ring_passq(q, k, v, q_pos, kv_pos, scale: Optional[float] = None):
-    """Algorithm 3. Queries circulate, KV stays.
+def ring_passq(q, k, v, q_pos, kv_pos, scale: Optional[float] = None, cu_q=None, cu_kv=None):
+    """Algorithm 3. Queries circulate, KV stays. cu_q / cu_kv as in ring_passkv.
 
     At step j rank k holds the queries that started on rank s = (k - j) mod N
     and computes their partial output against its own KV. The partials are
@@ -357,7 +361,9 @@ def ring_passq(q, k, v, q_pos, kv_pos, scale: Optional[float] = None):
         for kk in range(n):
             s = (kk - j) % n
             assert held[kk] == s
-            on_rank[kk][s] = attn(q[s], k[kk], v[kk], q_pos[s], kv_pos[kk], scale=scale)
+            on_rank[kk][s] = attn(q[s], k[kk], v[kk], q_pos[s], kv_pos[kk],
+                                  cu_q=None if cu_q is None else cu_q[s],
+                                  cu_kv=None if cu_kv is None else cu_kv[kk], scale=scale)
         held = [held[(kk - 1) % n] for kk in range(n)]
     # All2All: source rank s receives, from every rank k, the partial computed there
     part_o = [[on_rank[kk][s][0] for kk in range(n)] for s in range(n)]

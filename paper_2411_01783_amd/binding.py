@@ -57,7 +57,7 @@ class cp_ring_desc(ctypes.Structure):
                 ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp)),
                 ("aux_stream", _vp), ("message_layout", _i32),
                 ("arrived", ctypes.POINTER(_vp)), ("ring_error", _vp), ("spin_limit", _i32),
-                ("gathered_q", _i32)]
+                ("gathered_q", _i32), ("cu_seqlens_q", ctypes.POINTER(_vp))]
 
 
 class cp_select_params(ctypes.Structure):
@@ -395,10 +395,11 @@ class Ring:
                  bid: Optional[List[torch.Tensor]] = None, aux_stream=None,
                  fused_merge=False, message_layout: bool = False,
                  arrived: Optional[List[torch.Tensor]] = None, spin_limit: int = 1 << 20,
-                 gathered_q: bool = False):
+                 gathered_q: bool = False,
+                 cu_seqlens_q: Optional[List[torch.Tensor]] = None):
         n = len(q)
         self.n = n
-        self.decode = cu_seqlens_kv is not None
+        self.decode = cu_seqlens_kv is not None and cu_seqlens_q is None
         dev = q[0].device
         _, nh, d = q[0].shape
         nkv = k[0].shape[1]
@@ -461,6 +462,13 @@ class Ring:
             self.ring_error = torch.zeros(1, dtype=torch.int32, device=dev)
             dsc.ring_error = _ptr(self.ring_error)
             dsc.spin_limit = spin_limit
+        if cu_seqlens_q is not None:   # packed prefill batch
+            self._cuq = (_vp * n)(*[_ptr(t) for t in cu_seqlens_q])
+            self._cu = (_vp * n)(*[_ptr(t) for t in cu_seqlens_kv])
+            dsc.batch = cu_seqlens_q[0].numel() - 1
+            dsc.cu_seqlens_q = ctypes.cast(self._cuq, ctypes.POINTER(_vp))
+            dsc.cu_seqlens_kv = ctypes.cast(self._cu, ctypes.POINTER(_vp))
+            self.tensors = self.tensors + (cu_seqlens_q,)
         if self.decode:
             self._cu = (_vp * n)(*[_ptr(t) for t in cu_seqlens_kv])
             self._bid = (_vp * n)(*[(_ptr(t) if t.numel() > 0 else None) for t in bid])

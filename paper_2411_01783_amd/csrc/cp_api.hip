@@ -217,6 +217,12 @@ int cp_attn_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* c
 // ring drivers
 // ---------------------------------------------------------------------------
 
+// Prefill drivers over packed batches (the fused variable-length inputs of Algorithm 2): every
+// rank's Q and KV hold `batch` sequences back to back with per-rank cu_seqlens.
+static bool ring_is_packed(const cp_ring_desc* d, bool decode) {
+  return !decode && d->cu_seqlens_q != nullptr;
+}
+
 static int check_ring(const cp_ring_desc* d, bool decode) {
   if (d == nullptr) return CP_ERR_NULL;
   if (d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS) return CP_ERR_SHAPE;
@@ -241,9 +247,15 @@ static int check_ring(const cp_ring_desc* d, bool decode) {
   if (decode) {
     if (d->batch < 1 || d->cu_seqlens_kv == nullptr || d->bid == nullptr) return CP_ERR_NULL;
   }
+  const bool packed = ring_is_packed(d, decode);
+  if (packed) {
+    if (d->batch < 1) return CP_ERR_SHAPE;
+    if (d->cu_seqlens_kv == nullptr) return CP_ERR_NULL;
+    if (d->fused_merge || d->gathered_q || d->aux_stream != nullptr) return CP_ERR_UNSUPPORTED;
+  }
   cp_shape s = {};
   s.dtype = d->dtype; s.head_dim = d->head_dim; s.n_q_heads = d->n_q_heads;
-  s.n_kv_heads = d->n_kv_heads; s.batch = decode ? d->batch : 1;
+  s.n_kv_heads = d->n_kv_heads; s.batch = (decode || packed) ? d->batch : 1;
   s.softmax_scale = d->softmax_scale;
   int rc = check_shape(&s);
   if (rc != CP_OK) return rc;
@@ -255,6 +267,8 @@ static int check_ring(const cp_ring_desc* d, bool decode) {
       return CP_ERR_NULL;
     if (decode && (d->cu_seqlens_kv[r] == nullptr || (d->n_q[r] > 0 && d->bid[r] == nullptr)))
       return CP_ERR_NULL;
+    if (packed && (d->cu_seqlens_q[r] == nullptr || d->cu_seqlens_kv[r] == nullptr))
+      return CP_ERR_NULL;
   }
   return CP_OK;
 }
@@ -262,7 +276,7 @@ static int check_ring(const cp_ring_desc* d, bool decode) {
 static cp_shape ring_shape(const cp_ring_desc* d, int q_rank, int kv_rank, bool decode) {
   cp_shape s = {};
   s.dtype = d->dtype; s.head_dim = d->head_dim; s.n_q_heads = d->n_q_heads;
-  s.n_kv_heads = d->n_kv_heads; s.batch = decode ? d->batch : 1;
+  s.n_kv_heads = d->n_kv_heads; s.batch = (decode || ring_is_packed(d, decode)) ? d->batch : 1;
   s.total_q = d->n_q[q_rank]; s.total_kv = d->n_kv[kv_rank];
   s.softmax_scale = d->softmax_scale;
   return s;
@@ -272,7 +286,8 @@ static cp_shape ring_shape(const cp_ring_desc* d, int q_rank, int kv_rank, bool 
 // per driver call, reused by the N calls that read the shard), then the per-call workspace.
 static bool ring_uses_tile_bounds(const cp_ring_desc* d, bool decode) {
   cp_shape s = ring_shape(d, 0, 0, decode);
-  return !decode && mfma_prefill_applies(s);
+  // (a packed batch shifts its positions per call, so bounds of the raw positions are no use)
+  return !decode && !ring_is_packed(d, decode) && mfma_prefill_applies(s);
 }
 
 static size_t ring_bounds_bytes(const cp_ring_desc* d, bool decode) {
@@ -488,8 +503,11 @@ int ring_partial(const cp_ring_desc* d, const RingWork& w, bool decode, int a, i
                                w.call_ws_bytes, (char*)d->workspace + w.bounds_off[b], nullptr, st,
                                acc);
   }
-  return cp_attn_partial(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b], nullptr,
-                         nullptr, o, l, d->part_dtype, w.call_ws, w.call_ws_bytes, st);
+  const bool packed = ring_is_packed(d, decode);
+  return cp_attn_partial(&s, d->q[a], d->k[b], d->v[b], d->q_pos[a], d->kv_pos[b],
+                         packed ? d->cu_seqlens_q[a] : nullptr,
+                         packed ? d->cu_seqlens_kv[b] : nullptr, o, l, d->part_dtype, w.call_ws,
+                         w.call_ws_bytes, st);
 }
 
 int ring_merge(const cp_ring_desc* d, const RingSlots& slots, int a, int64_t first_slot,

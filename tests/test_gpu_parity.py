@@ -729,3 +729,56 @@ def test_ring_passq_gathered_queries_decode(oracle):
     torch.cuda.synchronize()
     for s in range(n):
         check(out[s], lse[s], ref_o[s], ref_l[s], what="gathered decode, source %d" % s)
+
+
+# ---------------------------------------------------------------------------
+# ring drivers over packed batches (fused variable-length inputs of Algorithm 2)
+# ---------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype,nh,nkv,d,lengths", [
+    ("bf16", 16, 1, 128, [700, 5, 1300, 64, 2048]),
+    ("bf16", 8, 2, 128, [333, 1, 900]),
+    ("fp32", 4, 1, 64, [100, 3, 257]),
+])
+def test_ring_drivers_over_a_packed_batch(oracle, dtype, nh, nkv, d, lengths):
+    n = 3
+    qs = [randn(800 + b, (L, nh, d), dtype) for b, L in enumerate(lengths)]
+    ks = [randn(820 + b, (L, nkv, d), dtype) for b, L in enumerate(lengths)]
+    vs = [randn(840 + b, (L, nkv, d), dtype) for b, L in enumerate(lengths)]
+    ref = [oracle.unsharded_causal(qs[b][1], ks[b][1], vs[b][1]) for b in range(len(lengths))]
+    pos = [[B.cp_shard_positions(L, n, r) for L in lengths] for r in range(n)]
+    cu = [np.concatenate([[0], np.cumsum([len(p) for p in pos[r]])]).astype(np.int32)
+          for r in range(n)]
+
+    def pack(src, r):
+        return torch.cat([src[b][0][pos[r][b]] for b in range(len(lengths))])
+    rq, rk, rv = ([pack(x, r) for r in range(n)] for x in (qs, ks, vs))
+    rpos = [np.concatenate(pos[r]) for r in range(n)]
+    atol, rtol = (2e-2, 1e-3) if dtype == "bf16" else (O_ATOL_FP32, LSE_RTOL_FP32)
+    part_ref = oracle.ring_passkv([W.to_f64(x) for x in rq], [W.to_f64(x) for x in rk],
+                                  [W.to_f64(x) for x in rv], rpos, rpos, cu_q=cu, cu_kv=cu)
+    for order in (B.cp_ring_passkv, B.cp_ring_passq):
+        for keep in (False, True):
+            ring = B.Ring([dev(x) for x in rq], [dev(x) for x in rk], [dev(x) for x in rv],
+                          [i32(p) for p in rpos], [i32(p) for p in rpos],
+                          out_dtype=torch.float32, keep_partials=keep,
+                          cu_seqlens_q=[i32(c) for c in cu], cu_seqlens_kv=[i32(c) for c in cu])
+            out, lse = order(ring)
+            torch.cuda.synchronize()
+            for r in range(n):
+                for b in range(len(lengths)):
+                    sl = slice(cu[r][b], cu[r][b + 1])
+                    check(out[r][sl], lse[r][sl], ref[b][0][pos[r][b]], ref[b][1][pos[r][b]],
+                          o_atol=atol, lse_rtol=rtol,
+                          what="%s rank %d sequence %d" % (order.__name__, r, b))
+            if keep:   # the per-(rank, shard) partials too
+                for a in range(n):
+                    for s in range(n):
+                        po, pl = ring.partial(a, s)
+                        check(po, pl, part_ref[2][a][s], part_ref[3][a][s], o_atol=atol,
+                              lse_rtol=rtol, what="partial %d,%d" % (a, s))
+    with pytest.raises(B.CpError):   # the fused modes take one sequence only
+        B.cp_ring_passkv(B.Ring([dev(x) for x in rq], [dev(x) for x in rk], [dev(x) for x in rv],
+                                [i32(p) for p in rpos], [i32(p) for p in rpos], fused_merge=True,
+                                cu_seqlens_q=[i32(c) for c in cu],
+                                cu_seqlens_kv=[i32(c) for c in cu]))

@@ -416,6 +416,45 @@ def test_batched_decode_is_independent_of_owner_rank(oracle, decode_iter):
     assert seen == set(range(len(lengths)))
 
 
+def shard_packed_batch(oracle, lengths, n):
+    """Per rank: the packed positions of its share of every sequence and the boundaries."""
+    pos, cu = [], []
+    for r in range(n):
+        parts = [oracle.shard_positions(L, n, r) for L in lengths]
+        pos.append(parts)
+        cu.append(np.concatenate([[0], np.cumsum([len(p) for p in parts])]).astype(np.int32))
+    return pos, cu
+
+
+@pytest.mark.parametrize("n", [1, 2, 3])
+def test_ring_over_a_packed_batch_reproduces_every_sequence(oracle, n):
+    # Algorithm 2 / 3 on fused variable-length inputs: each rank holds its load-balanced share
+    # of every sequence; a sequence shorter than 2N leaves some ranks an empty segment
+    nh, d = 4, 8
+    lengths = [23, 1, 9, 40, 2]
+    qs = [rnd(300 + b, L, nh, d) for b, L in enumerate(lengths)]
+    ks = [rnd(320 + b, L, 2, d) for b, L in enumerate(lengths)]
+    vs = [rnd(340 + b, L, 2, d) for b, L in enumerate(lengths)]
+    ref = [oracle.unsharded_causal(qs[b], ks[b], vs[b]) for b in range(len(lengths))]
+    pos, cu = shard_packed_batch(oracle, lengths, n)
+
+    def pack(src, r):
+        return np.concatenate([src[b][pos[r][b]] for b in range(len(lengths))])
+    args = ([pack(qs, r) for r in range(n)], [pack(ks, r) for r in range(n)],
+            [pack(vs, r) for r in range(n)], [np.concatenate(pos[r]) for r in range(n)],
+            [np.concatenate(pos[r]) for r in range(n)])
+    for ring in (oracle.ring_passkv, oracle.ring_passq):
+        out, lse, _, _ = ring(*args, cu_q=cu, cu_kv=cu)
+        for r in range(n):
+            for b in range(len(lengths)):
+                sl = slice(cu[r][b], cu[r][b + 1])
+                np.testing.assert_allclose(out[r][sl], ref[b][0][pos[r][b]], atol=1e-12)
+                np.testing.assert_allclose(lse[r][sl], ref[b][1][pos[r][b]], atol=1e-12)
+    # without the boundaries the sequences would see each other: the pin notices
+    out, _, _, _ = oracle.ring_passkv(*args)
+    assert not np.allclose(out[0][cu[0][3]:cu[0][4]], ref[3][0][pos[0][3]])
+
+
 # ---------------------------------------------------------------------------
 # persistent KV cache over several turns (Sections 3.5.2, 3.6)
 # ---------------------------------------------------------------------------
