@@ -109,6 +109,32 @@ def test_mfma_partial_random_positions(oracle, tq, tkv, nh, nkv):
         check(o, l, *ref, what="out dtype %s" % odt)
 
 
+def test_mfma_partial_seeded_shape_sweep(oracle):
+    """Twelve seeded shapes inside the documented limits: ragged row blocks and tiles, every
+    head grouping, split and unsplit walks, sorted and shuffled positions, pads."""
+    rng = np.random.default_rng(2024)
+    for case in range(12):
+        nkv = int(rng.choice([1, 1, 2, 4]))
+        group = int(rng.choice([1, 2, 4, 8, 16]))
+        nh = nkv * group
+        tq = int(rng.integers(1, 700)) if case % 3 else int(rng.integers(2048, 2600))
+        tkv = int(rng.integers(1, 1500))
+        q, q64 = randn(900 + case, (tq, nh, 128))
+        k, k64 = randn(930 + case, (tkv, nkv, 128))
+        v, v64 = randn(960 + case, (tkv, nkv, 128))
+        if case % 2:
+            kp = np.sort(rng.choice(3 * tkv, size=tkv, replace=False))     # a sorted shard
+            qp = np.sort(rng.integers(0, 3 * tkv, size=tq))
+        else:
+            kp = rng.permutation(tkv + 50)[:tkv]
+            qp = rng.integers(-1, tkv + 40, size=tq)
+        if tkv > 8:
+            kp[rng.integers(0, tkv, size=3)] = B.CP_POS_PAD_KV
+        ref = oracle.attn(q64, k64, v64, qp, kp)
+        o, l = gpu_partial(q, k, v, qp, kp, out_dtype=torch.float32)
+        check(o, l, *ref, what="case %d: tq %d tkv %d heads %d/%d" % (case, tq, tkv, nh, nkv))
+
+
 @pytest.mark.parametrize("nh,nkv", [(16, 1), (8, 2)])
 def test_mfma_packed_batch_random_positions(oracle, nh, nkv):
     # Algorithm 2's fused variable-length inputs: several sequences in one call, one of them
