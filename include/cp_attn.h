@@ -279,8 +279,8 @@ typedef struct {
    * reads of the shard after the flag but invalidates no cache, so every step's shard needs
    * a buffer of its own that is complete before its flag is set and is not written again
    * while the kernel runs (N receive buffers per rank instead of two). The wait is bounded:
-   * one thread per workgroup polls at most spin_limit (>= 1) times, a few hundred cycles
-   * apart; if the flag stays zero the workgroup leaves that shard out and sets *ring_error
+   * one thread per workgroup polls at most spin_limit (>= 1) times, a memory round trip and
+   * a short sleep (a few microseconds in all) apart; if the flag stays zero the workgroup leaves that shard out and sets *ring_error
    * (device int32, required with arrived; the caller zeroes it) to 1 - the outputs are then
    * not meaningful, but every kernel ends.
    */

@@ -394,7 +394,7 @@ class Ring:
                  cu_seqlens_kv: Optional[List[torch.Tensor]] = None,
                  bid: Optional[List[torch.Tensor]] = None, aux_stream=None,
                  fused_merge=False, message_layout: bool = False,
-                 arrived: Optional[List[torch.Tensor]] = None, spin_limit: int = 1 << 20,
+                 arrived: Optional[List[torch.Tensor]] = None, spin_limit: int = 1 << 16,
                  gathered_q: bool = False,
                  cu_seqlens_q: Optional[List[torch.Tensor]] = None):
         n = len(q)
