@@ -395,6 +395,43 @@ def mfma_rate_probe(iters: int = 20000, reps: int = 3):
     return out
 
 
+def bench_paper_step_shapes(reps: int = 10):
+    """One ring step at the two shapes whose attention time the paper prints (its breakdown
+    table for P + T = 128000 on CP4: T = 3200 and T = 12800, i.e. 800 / 3200 query tokens x 16
+    heads against a 32000-token KV shard): context next to the H100 figures, not a target."""
+    rows = []
+    n = 4
+    for t_new, paper_us in ((3200, 414.0), (12800, 1608.0)):
+        p_cached = 128000 - t_new
+        qp = [B.cp_shard_positions(t_new, n, r, offset=p_cached) for r in range(n)]
+        kvp = [np.concatenate([B.cp_shard_positions(p_cached, n, r), qp[r]]) for r in range(n)]
+        q = W.normal(81, (len(qp[0]), 16, 128), "bf16", "cuda")
+        k = W.normal(82, (len(kvp[1]), 1, 128), "bf16", "cuda")
+        v = W.normal(83, (len(kvp[1]), 1, 128), "bf16", "cuda")
+        q_pos, kv_pos = _i32(qp[0]), _i32(kvp[1])
+        shape = B.make_shape(B.CP_BF16, 128, 16, 1, q.shape[0], k.shape[0])
+        ws = torch.empty(B.cp_workspace_bytes(shape, B.CP_WS_PARTIAL) + 256, dtype=torch.uint8,
+                         device="cuda")
+        out = torch.empty((q.shape[0], 16, 128), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((q.shape[0], 16), dtype=torch.float32, device="cuda")
+
+        def call():
+            B.cp_attn_partial(q, k, v, q_pos, kv_pos, out=out, lse=lse, workspace=ws)
+        call()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        flop = 4.0 * 128 * 16 * visible_pairs(qp[0], kvp[1])
+        rows.append({"t_new": t_new, "q_tokens": int(q.shape[0]), "kv_tokens": int(k.shape[0]),
+                     "us": round(us, 1), "tflops": round(flop / us / 1e6, 1),
+                     "paper_h100_us": paper_us})
+    return rows
+
+
 def hbm_read_probe(nbytes: int, n_buffers: int = 16, reps: int = 5):
     """What one launch that only reads `nbytes` once achieves (ramp and tail included), cycling
     over `n_buffers` buffers as the decode measurement cycles over the ranks' KV (no reuse from
@@ -608,6 +645,7 @@ def main():
         result["aux"]["partial_prefill"] = bench_partial_prefill(
             ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
              "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"])
+        result["aux"]["paper_step_shapes"] = bench_paper_step_shapes()
         result["aux"]["kv_append"] = bench_kv_append()
         result["aux"]["selector"] = selector_table(tflops * 1e12)
         result["aux"]["mfma_rate_probe"] = mfma_rate_probe()

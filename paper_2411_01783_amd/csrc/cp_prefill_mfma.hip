@@ -163,8 +163,24 @@ Plan make_plan(const cp_shape& s) {
   const int64_t wgs = (int64_t)pl.n_row_blocks * s.n_kv_heads;
   int splits = 1;
   if (wgs > 0 && wgs < 128 && pl.n_tiles >= 2 * kMinTilesPerSplit) {
-    splits = (int)std::min<int64_t>((256 + wgs - 1) / wgs, pl.n_tiles / kMinTilesPerSplit);
-    splits = std::max(1, std::min(splits, CP_MAX_PARTS));
+    // Cost of a split count, in units of one tile step of a workgroup: the workgroups run in
+    // rounds of 256 (one per CU), each round walks its tiles plus about three tile steps of
+    // start-up and epilogue, and every split adds one fp32 partial to write and to merge.
+    const int max_splits = (int)std::min<int64_t>(pl.n_tiles / kMinTilesPerSplit, CP_MAX_PARTS);
+    const double partial_cost = (double)s.total_q * s.n_q_heads * 4.8e-5;
+    double best = 0.0;
+    for (int c = 1; c <= max_splits; ++c) {
+      const int tps = (pl.n_tiles + c - 1) / c;
+      const int ns = (pl.n_tiles + tps - 1) / tps;
+      if (ns != c) continue;  // the same split as a smaller count
+      const int64_t rounds = (wgs * ns + 255) / 256;
+      const double cost = (double)rounds * (tps + 3) + partial_cost * ns;
+      if (splits == 1 && c == 1) best = cost;
+      if (cost < best) {
+        best = cost;
+        splits = c;
+      }
+    }
   }
   pl.tiles_per_split = pl.n_tiles > 0 ? (pl.n_tiles + splits - 1) / splits : 1;
   pl.n_splits = pl.n_tiles > 0 ? (pl.n_tiles + pl.tiles_per_split - 1) / pl.tiles_per_split : 1;
