@@ -493,6 +493,11 @@ def main():
                     choices=["prefill_128k", "prefill_1m"])
     ap.add_argument("--no-aux", action="store_true", help="skip the decode measurement")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--zero-inputs", action="store_true",
+                    help="also time the headline's launches on all-zero Q, K, V (the kernel's "
+                         "efficiency in cycles: the part holds its full clock on such data); off "
+                         "by default so that a kernel trace of the default run holds the ring "
+                         "walk on N(0,1) data only")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="run one ring pass, one decode pass and a plain streaming kernel of "
                          "known size, then exit (the workload of the rocprofv3 --pmc runs)")
@@ -595,19 +600,20 @@ def main():
             "tflops": round(flop_step / secw / 1e12, 2),
             "ms_per_rank": round(secw * 1e3 / w.n_ranks, 3)}
         del walk
-        # the headline's launches on all-zero Q, K, V (same positions, same tile walk, same
-        # instruction stream): the part then holds its full clock, so this is the kernel's
-        # efficiency in cycles; with N(0,1) data the matrix pipe's switching activity lowers
-        # the clock (see mfma_rate_probe) and the same cycles take longer
-        zeros = B.Ring([torch.zeros_like(x) for x in st["qs"]],
-                       [torch.zeros_like(x) for x in st["ks"]],
-                       [torch.zeros_like(x) for x in st["vs"]], st["ps"], st["ps"],
-                       out_dtype=torch.bfloat16, fused_merge=2)
-        secz = time_steps(lambda: B.cp_ring_passkv(zeros), args.steps, args.warmup)
-        result["aux"]["ring_walk_on_zero_inputs"] = {
-            "tflops": round(flop_step / secz / 1e12, 2),
-            "frac_of_peak": round(flop_step / secz / 1e12 / PEAK_BF16_TFLOPS, 4)}
-        del zeros
+        if args.zero_inputs:
+            # the headline's launches on all-zero Q, K, V (same positions, same tile walk, same
+            # instruction stream): the part then holds its full clock, so this is the kernel's
+            # efficiency in cycles; with N(0,1) data the matrix pipe's switching activity lowers
+            # the clock (see mfma_rate_probe) and the same cycles take longer
+            zeros = B.Ring([torch.zeros_like(x) for x in st["qs"]],
+                           [torch.zeros_like(x) for x in st["ks"]],
+                           [torch.zeros_like(x) for x in st["vs"]], st["ps"], st["ps"],
+                           out_dtype=torch.bfloat16, fused_merge=2)
+            secz = time_steps(lambda: B.cp_ring_passkv(zeros), args.steps, args.warmup)
+            result["aux"]["ring_walk_on_zero_inputs"] = {
+                "tflops": round(flop_step / secz / 1e12, 2),
+                "frac_of_peak": round(flop_step / secz / 1e12 / PEAK_BF16_TFLOPS, 4)}
+            del zeros
         # context: the same per-rank result from ONE launch per rank over the whole sequence's
         # K/V in natural order (what an all-gather of KV instead of a ring would run): no ring
         # steps, so none of their per-launch start-up, epilogue and merge traffic
