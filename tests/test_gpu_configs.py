@@ -105,6 +105,31 @@ def test_prefill_1m_one_rank_sampled(oracle):
     assert rel_l2(out[sel], ref_o) < 2e-2
 
 
+def test_prefill_1m_ring_walk_sampled(oracle):
+    # the 1M-token ring in the configuration bench.py --workload prefill_1m times: every
+    # rank's 16 ring steps in one launch behind arrival flags
+    w = W.WORKLOADS["prefill_1m"]
+    q, k, v = W.qkv(w, device="cuda")
+    n = w.n_ranks
+    pos, qs, ks, vs = _shard(w, q, k, v)
+    ps = [i32(p) for p in pos]
+    flags = [torch.ones(n, dtype=torch.int32, device="cuda") for _ in range(n)]
+    ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, fused_merge=2, arrived=flags)
+    out, lse = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    assert int(ring.ring_error.item()) == 0
+    k64, v64 = W.to_f64(k), W.to_f64(v)
+    rng = np.random.default_rng(w.seed + 1)
+    chunk = w.t_new // (2 * n)
+    for r in (0, 9):
+        rows = _sample_rows(len(pos[r]), chunk, rng, extra=2)
+        tok = pos[r][rows]
+        ref_o, ref_l = oracle.attn(_gather_f64(q, tok), k64, v64, tok, np.arange(w.t_new))
+        sel = torch.as_tensor(rows).to("cuda")
+        check(out[r][sel], lse[r][sel], ref_o, ref_l, what="rank %d" % r)
+        assert rel_l2(out[r][sel], ref_o) < 2e-2
+
+
 @pytest.mark.parametrize("gathered", [False, True])
 @pytest.mark.parametrize("name", ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
                                   "partial_prefill_128k_t8192"])
