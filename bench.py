@@ -487,8 +487,8 @@ def stored_traffic(kernel: str, workload: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="prefill_128k",
                     choices=["prefill_128k", "prefill_1m"])
     ap.add_argument("--no-aux", action="store_true", help="skip the decode measurement")
