@@ -307,3 +307,28 @@ def test_select_order_rejects_bad_arguments(lib):
     bad = B.cp_select_params(16, 1, 4, 0, 0.0, 1e11, 2.0, 0.0, 0.0, 0.0)
     assert f(ctypes.byref(bad), 1, 0, 0, ctypes.byref(out)) == -2
     assert f(ctypes.byref(bad), 1, 0, 2, ctypes.byref(out)) == 0   # empirical rule needs no C / BW
+
+
+def test_ctypes_structs_match_the_header_layout(tmp_path):
+    """The binding's ctypes mirrors of cp_shape, cp_ring_desc and cp_select_params have the
+    size and field offsets the C compiler gives the header's structs."""
+    import subprocess
+    structs = {"cp_shape": B.cp_shape, "cp_ring_desc": B.cp_ring_desc,
+               "cp_select_params": B.cp_select_params}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "cp_attn.h"', 'int main(void) {']
+    for name, cls in structs.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (name, name))
+        for field, _ in cls._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (name, field, name, field))
+    lines += ['return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o",
+                    str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout
+    got = dict(line.split() for line in out.strip().splitlines())
+    for name, cls in structs.items():
+        assert int(got[name]) == ctypes.sizeof(cls), name
+        for field, _ in cls._fields_:
+            assert int(got["%s.%s" % (name, field)]) == getattr(cls, field).offset, (name, field)
