@@ -279,31 +279,39 @@ def test_ring_walk_in_one_launch_matches_unsharded(oracle, n, t, flags):
     # (t = 7001: shards of 2334, 2334 and 2333 tokens, ragged last tiles)
     rows = np.r_[0:48, t // 4 - 6:t // 4 + 6, t // 2 - 5:t // 2 + 5, t - 3 * t // 8:t - 3 * t // 8 + 16,
                  t - 48:t]
+    # one padded query row (sees nothing in any shard): token 5, the sixth row of rank 0
+    rows = rows[rows != 5]
+    q_pos = [p.copy() for p in pos]
+    assert pos[0][5] == 5
+    q_pos[0][5] = B.CP_POS_PAD_Q
     ref_o, ref_l = oracle.attn(q64[rows], k64, v64, rows, np.arange(t))
     where = {int(p): (a, i) for a in range(n) for i, p in enumerate(pos[a])}
     for odt in (torch.float32, torch.bfloat16):
         arrived = [torch.ones(n, dtype=torch.int32, device="cuda") for _ in range(n)] \
             if flags else None
         ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos], [dev(v[p]) for p in pos],
-                      [i32(p) for p in pos], [i32(p) for p in pos], out_dtype=odt,
+                      [i32(p) for p in q_pos], [i32(p) for p in pos], out_dtype=odt,
                       fused_merge=2, arrived=arrived, spin_limit=1000)
         out, lse = B.cp_ring_passkv(ring)
         torch.cuda.synchronize()
         if flags:
             assert int(ring.ring_error.item()) == 0
+        assert torch.isneginf(lse[0][5]).all() and (out[0][5] == 0).all()
         got_o = torch.stack([out[where[int(r)][0]][where[int(r)][1]] for r in rows])
         got_l = torch.stack([lse[where[int(r)][0]][where[int(r)][1]] for r in rows])
         check(got_o, got_l, ref_o, ref_l, what="ring walk, %s" % odt)
         # the step-by-step ring with the merge in the epilogues computes the same thing
         if odt == torch.float32:
             step = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in pos],
-                          [dev(v[p]) for p in pos], [i32(p) for p in pos], [i32(p) for p in pos],
+                          [dev(v[p]) for p in pos], [i32(p) for p in q_pos], [i32(p) for p in pos],
                           out_dtype=odt, fused_merge=True)
             out_s, lse_s = B.cp_ring_passkv(step)
             torch.cuda.synchronize()
             for a in range(n):
                 assert float((out[a] - out_s[a]).abs().max()) < 2e-3
-                assert float((lse[a] - lse_s[a]).abs().max()) < 1e-4
+                fin = torch.isfinite(lse[a])
+                assert torch.equal(fin, torch.isfinite(lse_s[a]))
+                assert float((lse[a][fin] - lse_s[a][fin]).abs().max()) < 1e-4
     with pytest.raises(B.CpError):   # pass-Q moves the queries: no such walk
         B.cp_ring_passq(ring)
 
