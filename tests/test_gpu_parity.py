@@ -816,3 +816,34 @@ def test_ring_drivers_over_a_packed_batch(oracle, dtype, nh, nkv, d, lengths):
                                 [i32(p) for p in rpos], [i32(p) for p in rpos], fused_merge=True,
                                 cu_seqlens_q=[i32(c) for c in cu],
                                 cu_seqlens_kv=[i32(c) for c in cu]))
+
+
+def test_positions_close_to_the_int32_limit(oracle):
+    """Positions are compared as int32: a sequence whose positions end two below the pad value
+    behaves like the same sequence at zero (MFMA partial, decode, vector kernel)."""
+    t, nh = 700, 16
+    base = B.CP_POS_PAD_KV - 1 - t           # last position = INT32_MAX - 2
+    q, q64 = randn(171, (t, nh, 128))
+    k, k64 = randn(172, (t, 1, 128))
+    v, v64 = randn(173, (t, 1, 128))
+    rng = np.random.default_rng(3)
+    kp = rng.permutation(t)
+    qp = rng.integers(0, t, size=t)
+    ref = oracle.attn(q64, k64, v64, qp, kp)
+    o, l = gpu_partial(q, k, v, qp + base, kp + base, out_dtype=torch.float32)
+    check(o, l, *ref, what="MFMA partial at the int32 limit")
+    # decode: one query at the last position against the whole sequence
+    od, ld = B.cp_attn_decode(dev(q[:1]), dev(k), dev(v), i32([base + t - 1]), i32(kp + base),
+                              i32([0, t]), i32([0]), out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    rd = oracle.attn(q64[:1], k64, v64, [t - 1], kp)
+    check(od, ld, *rd, what="decode at the int32 limit")
+    # fp32 vector kernel
+    qf, qf64 = randn(174, (40, 4, 64), "fp32")
+    kf, kf64 = randn(175, (90, 1, 64), "fp32")
+    vf, vf64 = randn(176, (90, 1, 64), "fp32")
+    qpf, kpf = rng.integers(0, 90, size=40), rng.permutation(90)
+    big = B.CP_POS_PAD_KV - 1 - 90
+    o, l = gpu_partial(qf, kf, vf, qpf + big, kpf + big, out_dtype=torch.float32)
+    check(o, l, *oracle.attn(qf64, kf64, vf64, qpf, kpf), o_atol=O_ATOL_FP32,
+          lse_rtol=LSE_RTOL_FP32, what="vector kernel at the int32 limit")
