@@ -379,6 +379,17 @@ int cp_select_order(const cp_select_params* params, int64_t t_new, int64_t p_cac
                     int32_t rule, int32_t* order_out);
 
 /*
+ * Prefill with the ring order chosen at run time, as the paper's system does (Section 3.3):
+ * t_new = the sum of desc->n_q, cp_select_order(params, t_new, p_cached, rule) picks
+ * pass-KV or pass-Q, and the matching driver runs on `desc` (which must be valid for it; a
+ * descriptor without options is valid for both). params->n_ranks must equal desc->n_ranks.
+ * *order_out (host, may be NULL) receives the order taken. Errors: those of cp_select_order
+ * and of the driver; CP_ERR_SHAPE if the rank counts differ or no rank has a query.
+ */
+int cp_ring_prefill(const cp_ring_desc* desc, const cp_select_params* params, int64_t p_cached,
+                    int32_t rule, int32_t* order_out, void* stream);
+
+/*
  * Persistent KV cache of one rank (Sections 3.5.2 and 3.6: the K/V of every turn's new tokens,
  * decode tokens included, stay in the cache of the rank that owns them and are read by the
  * later turns' partial prefill and decode).

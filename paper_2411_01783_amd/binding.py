@@ -26,7 +26,7 @@ EXPORTS = [
     "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_partial_accumulate",
     "cp_attn_decode",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
-    "cp_ring_workspace_bytes", "cp_ring_message_bytes", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
+    "cp_ring_workspace_bytes", "cp_ring_message_bytes", "cp_ring_prefill", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
     "cp_decode_owner", "cp_probe_mfma_rate", "cp_probe_hbm_read", "cp_strerror",
     "cp_version",
 ]
@@ -113,6 +113,9 @@ def load() -> ctypes.CDLL:
         fn.argtypes = [ctypes.POINTER(cp_ring_desc), _vp]
     lib.cp_ring_workspace_bytes.restype = ctypes.c_size_t
     lib.cp_ring_workspace_bytes.argtypes = [ctypes.POINTER(cp_ring_desc), _i32]
+    lib.cp_ring_prefill.restype = ctypes.c_int
+    lib.cp_ring_prefill.argtypes = [ctypes.POINTER(cp_ring_desc), ctypes.POINTER(cp_select_params),
+                                    _i64, _i32, ctypes.POINTER(_i32), _vp]
     lib.cp_ring_message_bytes.restype = ctypes.c_size_t
     lib.cp_ring_message_bytes.argtypes = [ctypes.POINTER(cp_ring_desc)]
     lib.cp_select_order.restype = ctypes.c_int
@@ -500,6 +503,18 @@ def cp_ring_passkv(ring: Ring, stream=None):
 def cp_ring_passq(ring: Ring, stream=None):
     _check(load().cp_ring_passq(ctypes.byref(ring.desc), _stream(stream)), "cp_ring_passq")
     return ring.out, ring.lse
+
+
+def cp_ring_prefill(ring: Ring, p_cached: int, n_q_heads: int, n_kv_heads: int,
+                    peak_flops: float, bandwidth: float, bytes_per_elem: float = 2.0,
+                    rule: int = CP_RULE_ANALYTIC, stream=None):
+    """Prefill in the order cp_select_order picks; returns (out, lse, order)."""
+    prm = cp_select_params(n_q_heads, n_kv_heads, ring.n, 0, peak_flops, bandwidth,
+                           bytes_per_elem, 0.0, 0.0, 0.0)
+    order = _i32(-1)
+    _check(load().cp_ring_prefill(ctypes.byref(ring.desc), ctypes.byref(prm), p_cached, rule,
+                                  ctypes.byref(order), _stream(stream)), "cp_ring_prefill")
+    return ring.out, ring.lse, int(order.value)
 
 
 def cp_ring_passq_decode(ring: Ring, stream=None):

@@ -699,4 +699,21 @@ int cp_ring_passq_decode(const cp_ring_desc* d, void* stream) {
   return ring_passq_common(d, true, stream);
 }
 
+int cp_ring_prefill(const cp_ring_desc* d, const cp_select_params* params, int64_t p_cached,
+                    int32_t rule, int32_t* order_out, void* stream) {
+  if (d == nullptr || params == nullptr) return CP_ERR_NULL;
+  if (d->n_ranks < 1 || d->n_ranks > CP_MAX_PARTS || d->n_q == nullptr) return CP_ERR_SHAPE;
+  if (params->n_ranks != d->n_ranks) return CP_ERR_SHAPE;
+  int64_t t_new = 0;
+  for (int r = 0; r < d->n_ranks; ++r) {
+    if (d->n_q[r] < 0) return CP_ERR_SHAPE;
+    t_new += d->n_q[r];
+  }
+  int32_t order = CP_ORDER_PASS_KV;
+  const int rc = cp_select_order(params, t_new, p_cached, rule, &order);
+  if (rc != CP_OK) return rc;
+  if (order_out != nullptr) *order_out = order;
+  return order == CP_ORDER_PASS_Q ? cp_ring_passq(d, stream) : cp_ring_passkv(d, stream);
+}
+
 }  // extern "C"

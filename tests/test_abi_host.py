@@ -105,6 +105,28 @@ def test_hbm_probe_rejects_bad_arguments_before_any_launch(lib):
     assert lib.cp_probe_hbm_read(ctypes.c_void_p(260), ctypes.c_size_t(1024), 1, one, None) == -6
 
 
+def test_ring_prefill_validates_before_launching(lib):
+    d = B.cp_ring_desc()
+    prm = B.cp_select_params(128, 8, 4, 0, 1e15, 5e10, 2.0, 0.0, 0.0, 0.0)
+    order = ctypes.c_int32(-1)
+    assert lib.cp_ring_prefill(None, ctypes.byref(prm), 0, 0, ctypes.byref(order), None) == -1
+    assert lib.cp_ring_prefill(ctypes.byref(d), None, 0, 0, ctypes.byref(order), None) == -1
+    d.n_ranks = 4
+    assert lib.cp_ring_prefill(ctypes.byref(d), ctypes.byref(prm), 0, 0, None, None) == -2  # n_q
+    n_q = (ctypes.c_int64 * 4)(0, 0, 0, 0)
+    d.n_q = ctypes.cast(n_q, type(d.n_q))
+    assert lib.cp_ring_prefill(ctypes.byref(d), ctypes.byref(prm), 0, 0, None, None) == -2  # T = 0
+    n_q[0] = 16
+    prm.n_ranks = 8
+    assert lib.cp_ring_prefill(ctypes.byref(d), ctypes.byref(prm), 0, 0, None, None) == -2
+    prm.n_ranks = 4
+    assert lib.cp_ring_prefill(ctypes.byref(d), ctypes.byref(prm), 0, 9, None, None) == -3  # rule
+    # a valid choice, then the driver's own validation (the descriptor has no arrays)
+    assert lib.cp_ring_prefill(ctypes.byref(d), ctypes.byref(prm), 0, 0, ctypes.byref(order),
+                               None) == -1
+    assert order.value == B.CP_ORDER_PASS_KV
+
+
 def test_version_and_strerror(lib):
     assert B.cp_version() >= 100
     assert B.strerror(0) == "ok"

@@ -847,3 +847,28 @@ def test_positions_close_to_the_int32_limit(oracle):
     o, l = gpu_partial(qf, kf, vf, qpf + big, kpf + big, out_dtype=torch.float32)
     check(o, l, *oracle.attn(qf64, kf64, vf64, qpf, kpf), o_atol=O_ATOL_FP32,
           lse_rtol=LSE_RTOL_FP32, what="vector kernel at the int32 limit")
+
+
+def test_ring_prefill_follows_the_selector(oracle):
+    """cp_ring_prefill runs the order the selection rule picks: pass-Q for a small partial
+    prefill behind a long cache, pass-KV for a full prefill; same exact result either way."""
+    n, nh, d = 4, 16, 128
+    for p_cached, t_new, expect in ((6000, 128, B.CP_ORDER_PASS_Q), (0, 2048, B.CP_ORDER_PASS_KV)):
+        q, q64 = randn(181, (t_new, nh, d))
+        k, k64 = randn(182, (p_cached + t_new, 1, d))
+        v, v64 = randn(183, (p_cached + t_new, 1, d))
+        ref_o, ref_l = oracle.unsharded_causal(q64, k64, v64, p_cached=p_cached)
+        sh = oracle.shard_partial_prefill(p_cached, t_new, n)
+        ring = B.Ring([dev(q[qp - p_cached]) for qp, _ in sh], [dev(k[kp]) for _, kp in sh],
+                      [dev(v[kp]) for _, kp in sh], [i32(qp) for qp, _ in sh],
+                      [i32(kp) for _, kp in sh], out_dtype=torch.float32)
+        # Llama3-405B heads, an attention rate and a link for which Equation 2 gives T >= 5120
+        out, lse, order = B.cp_ring_prefill(ring, p_cached, 128, 8, peak_flops=1.024e15,
+                                            bandwidth=50e9)
+        torch.cuda.synchronize()
+        name = {B.CP_ORDER_PASS_KV: "pass-KV", B.CP_ORDER_PASS_Q: "pass-Q"}[order]
+        assert order == expect
+        assert name == oracle.select_order(t_new, p_cached, 128, 8, n, 1.024e15, 50e9)
+        for r, (qp, _) in enumerate(sh):
+            check(out[r], lse[r], ref_o[qp - p_cached], ref_l[qp - p_cached],
+                  what="T %d rank %d" % (t_new, r))
