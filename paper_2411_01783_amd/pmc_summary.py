@@ -6,6 +6,11 @@ kernel, which reads and writes a known number of bytes; the factor is printed in
 summary.
 
 usage: python -m paper_2411_01783_amd.pmc_summary FETCH.csv WRITE.csv OUT_DIR WORKLOAD "CMD"
+
+A third run of the same probe with matrix-pipe and LDS counters is summarised by
+       python -m paper_2411_01783_amd.pmc_summary --mfma COUNTERS.csv OUT_DIR WORKLOAD "CMD"
+into <kernel>_<workload>_mfma_counters.txt: mean counter values per launch, the share of
+SIMD cycles with the matrix pipe busy, the clock the launch ran at and the FLOPs it executed.
 """
 from __future__ import annotations
 
@@ -41,7 +46,60 @@ def per_dispatch(path: str, counter: str):
     return {k: list(v.values()) for k, v in acc.items()}
 
 
+N_XCD, N_CU, SIMD_PER_CU = 8, 256, 4   # MI355X
+FLOP_PER_MOP = 512                      # SQ_INSTS_VALU_MFMA_MOPS_*: 512 operations per count
+
+
+def mfma_main():
+    path, out_dir, workload, cmd = sys.argv[2:6]
+    acc = collections.defaultdict(lambda: collections.defaultdict(lambda: collections.defaultdict(float)))
+    dur = collections.defaultdict(dict)
+    for r in csv.DictReader(open(path)):
+        tag = None
+        for k, t in KERNELS:
+            if k in r["Kernel_Name"]:
+                tag = t
+                break
+        if tag is None:
+            continue
+        acc[tag][r["Dispatch_Id"]][r["Counter_Name"]] += float(r["Counter_Value"])
+        dur[tag][r["Dispatch_Id"]] = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+    for tag, disp in sorted(acc.items()):
+        if not tag.startswith("prefill"):
+            continue  # launches of a few microseconds: the counters' window is not the kernel's
+        n = len(disp)
+        mean = collections.defaultdict(float)
+        for d in disp.values():
+            for c, v in d.items():
+                mean[c] += v / n
+        ns = sum(dur[tag].values()) / n
+        wl = workload if tag.startswith("prefill") or tag.endswith("_ring") else "decode_b32"
+        out = os.path.join(out_dir, "%s_%s_mfma_counters.txt" % (tag, wl))
+        with open(out, "w") as f:
+            f.write("command:\n  %s\n\n" % cmd)
+            f.write("kernel: %s   workload: %s   dispatches: %d   mean duration %.1f us\n"
+                    % (tag, wl, n, ns / 1e3))
+            for c in sorted(mean):
+                f.write("  %-32s %.4g per launch\n" % (c, mean[c]))
+            cycles = mean.get("GRBM_GUI_ACTIVE", 0.0) / N_XCD   # summed over the XCDs
+            if cycles > 0:
+                f.write("clock during the launch: %.2f GHz (GRBM_GUI_ACTIVE / %d XCDs / duration)\n"
+                        % (cycles / ns, N_XCD))
+                busy = mean.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0)
+                f.write("matrix pipe busy: %.1f %% of SIMD cycles (SQ_VALU_MFMA_BUSY_CYCLES / "
+                        "(cycles x %d CUs x %d SIMDs))\n"
+                        % (100.0 * busy / (cycles * N_CU * SIMD_PER_CU), N_CU, SIMD_PER_CU))
+            mops = mean.get("SQ_INSTS_VALU_MFMA_MOPS_BF16", 0.0)
+            if mops > 0:
+                f.write("bf16 MFMA operations executed: %.4g FLOP per launch (%d per counted MOP), "
+                        "%.1f TFLOP/s over the mean duration\n"
+                        % (mops * FLOP_PER_MOP, FLOP_PER_MOP, mops * FLOP_PER_MOP / ns / 1e3))
+        print(out)
+
+
 def main():
+    if len(sys.argv) > 1 and sys.argv[1] == "--mfma":
+        return mfma_main()
     fetch_csv, write_csv, out_dir, workload, cmd = sys.argv[1:6]
     copy_bytes = 1 << 28
     rd = per_dispatch(fetch_csv, "FETCH_SIZE")
