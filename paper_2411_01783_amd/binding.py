@@ -487,6 +487,13 @@ class Ring:
         wp, wn = _ws_ptr(self.workspace)
         dsc.workspace, dsc.workspace_bytes = wp, wn
 
+    def arrival_failed(self) -> bool:
+        """True if a ring walk gave up waiting for a shard (synchronises the device)."""
+        if self.arrived is None:
+            return False
+        torch.cuda.synchronize()
+        return int(self.ring_error.item()) != 0
+
     def partial(self, a: int, b: int):
         """Partial (O, LSE) of rank a's queries against rank b's KV (keep_partials only)."""
         assert self.keep

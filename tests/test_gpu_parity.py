@@ -331,7 +331,7 @@ def test_ring_walk_gives_up_on_a_shard_that_never_arrives(oracle):
                   fused_merge=2, arrived=arrived, spin_limit=3)
     out, lse = B.cp_ring_passkv(ring)
     torch.cuda.synchronize()
-    assert int(ring.ring_error.item()) == 1
+    assert int(ring.ring_error.item()) == 1 and ring.arrival_failed()
     rows = np.r_[0:16, 1000:1016, 2032:2048]
     for a in (0, 1, 3):
         tok = pos[a][rows]
