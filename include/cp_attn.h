@@ -18,7 +18,9 @@
  *     h / (n_q_heads / n_kv_heads).
  *   - Pointers marked (device) are HIP device pointers owned by the caller; the
  *     library never allocates, frees or retains device memory and keeps no
- *     state between calls. Pointers marked (host) are read during the call only.
+ *     state between calls (the one exception, a scratch array inside the
+ *     library's device image, is described at cp_attn_decode_static). Pointers
+ *     marked (host) are read during the call only.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream) and the call returns without synchronising.
  *   - The return value is CP_OK (0) or a negative cp_status. Arguments are
@@ -174,6 +176,30 @@ int cp_attn_decode(const cp_shape* shape, const void* q, const void* k, const vo
                    const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_kv,
                    const int32_t* bid, void* out, float* lse, int32_t out_dtype,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * cp_attn_decode for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same
+ * computation, arguments, kernels and results as cp_attn_decode, but the split-KV partials go
+ * to a scratch array that is part of the library's device image (CP_STATIC_SCRATCH_BYTES per
+ * GPU the library runs on, held until the process ends) instead of a caller's workspace. The
+ * call allocates and frees nothing; the array's address on the current device is looked up on
+ * the first call on that device (hipGetSymbolAddress) and kept.
+ *   - CP_ERR_WORKSPACE if cp_workspace_bytes(shape, CP_WS_DECODE) exceeds
+ *     CP_STATIC_SCRATCH_BYTES (nothing is launched); CP_ERR_LAUNCH if the address lookup fails;
+ *     otherwise the errors of cp_attn_decode.
+ *   - Every call on a GPU uses that GPU's one array. Calls on one stream are ordered and safe;
+ *     calls that may overlap on one GPU (different streams without an event between them, or
+ *     several host threads on different streams) race on it: the caller must order them.
+ *   - Nothing in the array has to be cleared between calls: every launch writes each partial
+ *     it later reads.
+ * This is the library's only state; all other entry points keep none.
+ */
+#define CP_STATIC_SCRATCH_BYTES (8u << 20)
+int cp_attn_decode_static(const cp_shape* shape, const void* q, const void* k, const void* v,
+                          const int32_t* q_pos, const int32_t* kv_pos,
+                          const int32_t* cu_seqlens_kv, const int32_t* bid, void* out, float* lse,
+                          int32_t out_dtype, void* stream);
 
 /*
  * Merge attention, Appendix B Equation 4:

@@ -24,13 +24,14 @@ CP_MAX_PARTS = 64
 
 EXPORTS = [
     "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_partial_accumulate",
-    "cp_attn_decode",
+    "cp_attn_decode", "cp_attn_decode_static",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
     "cp_ring_workspace_bytes", "cp_ring_message_bytes", "cp_ring_prefill", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
     "cp_decode_owner", "cp_probe_mfma_rate", "cp_probe_hbm_read", "cp_strerror",
     "cp_version",
 ]
 CP_PROBE_OPERAND_BYTES = 65536
+CP_STATIC_SCRATCH_BYTES = 8 << 20
 
 _vp = ctypes.c_void_p
 _i32, _i64, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
@@ -104,6 +105,9 @@ def load() -> ctypes.CDLL:
     lib.cp_attn_decode.restype = ctypes.c_int
     lib.cp_attn_decode.argtypes = [ctypes.POINTER(cp_shape), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                    _vp, _vp, _i32, _vp, ctypes.c_size_t, _vp]
+    lib.cp_attn_decode_static.restype = ctypes.c_int
+    lib.cp_attn_decode_static.argtypes = [ctypes.POINTER(cp_shape), _vp, _vp, _vp, _vp, _vp, _vp,
+                                          _vp, _vp, _vp, _i32, _vp]
     lib.cp_attn_merge.restype = ctypes.c_int
     lib.cp_attn_merge.argtypes = [_i64, _i32, _i32, ctypes.POINTER(_vp), ctypes.POINTER(_vp),
                                   _i32, _vp, _i32, _vp, _vp]
@@ -314,6 +318,21 @@ def cp_attn_decode(q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid,
                               _ptr(kv_pos), _ptr(cu_seqlens_kv), _ptr(bid), _ptr(out), _ptr(lse),
                               dtype_code(out.dtype), wp, wn, _stream(stream)),
            "cp_attn_decode")
+    return out, lse
+
+
+def cp_attn_decode_static(q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid, out, lse,
+                          softmax_scale: float = 0.0, stream=None):
+    """cp_attn_decode into caller-provided `out` / `lse`, with the library's own scratch array
+    in place of a workspace: the call allocates nothing (nor does this wrapper)."""
+    nq, nh, d = q.shape
+    tkv, nkv, _ = k.shape
+    shape = make_shape(dtype_code(q.dtype), d, nh, nkv, nq, tkv, cu_seqlens_kv.numel() - 1,
+                       softmax_scale)
+    _check(load().cp_attn_decode_static(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v),
+                                        _ptr(q_pos), _ptr(kv_pos), _ptr(cu_seqlens_kv), _ptr(bid),
+                                        _ptr(out), _ptr(lse), dtype_code(out.dtype),
+                                        _stream(stream)), "cp_attn_decode_static")
     return out, lse
 
 

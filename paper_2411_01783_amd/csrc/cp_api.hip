@@ -2,6 +2,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 #include "cp_common.h"
@@ -35,6 +36,36 @@ inline bool mfma_prefill_applies(const cp_shape& s) {
 }
 
 inline size_t elem_size(int32_t dtype) { return dtype == CP_FP32 ? 4 : 2; }
+
+}  // namespace
+
+// Scratch of cp_attn_decode_static: split-KV partials live here instead of in a caller's
+// workspace, so that the call allocates nothing. Every GPU holds its own copy of the array at
+// its own address; in host code the array's name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[CP_STATIC_SCRATCH_BYTES];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CP_ERR_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) {
+      (void)hipGetLastError();
+      return CP_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return CP_OK;
+}
 
 }  // namespace
 
@@ -163,10 +194,13 @@ int cp_attn_partial_accumulate(const cp_shape* shape, const void* q, const void*
                              nullptr, (hipStream_t)stream, &acc);
 }
 
-int cp_attn_decode(const cp_shape* shape, const void* q, const void* k, const void* v,
-                   const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_kv,
-                   const int32_t* bid, void* out, float* lse, int32_t out_dtype,
-                   void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks shared by cp_attn_decode and cp_attn_decode_static. Returns CP_OK with
+// *launch = false when there is nothing to do.
+static int check_decode(const cp_shape* shape, const void* q, const void* k, const void* v,
+                        const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_kv,
+                        const int32_t* bid, const void* out, const float* lse, int32_t out_dtype,
+                        bool* launch) {
+  *launch = false;
   int rc = check_shape(shape);
   if (rc != CP_OK) return rc;
   const cp_shape& s = *shape;
@@ -180,13 +214,43 @@ int cp_attn_decode(const cp_shape* shape, const void* q, const void* k, const vo
   if (s.total_q > 0 && s.total_kv > 0 && (k == nullptr || v == nullptr || kv_pos == nullptr))
     return CP_ERR_NULL;
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return CP_ERR_ALIGN;
-  if (s.total_q == 0) return CP_OK;
+  *launch = s.total_q > 0;
+  return CP_OK;
+}
+
+int cp_attn_decode(const cp_shape* shape, const void* q, const void* k, const void* v,
+                   const int32_t* q_pos, const int32_t* kv_pos, const int32_t* cu_seqlens_kv,
+                   const int32_t* bid, void* out, float* lse, int32_t out_dtype,
+                   void* workspace, size_t workspace_bytes, void* stream) {
+  bool launch = false;
+  const int rc = check_decode(shape, q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid, out, lse,
+                              out_dtype, &launch);
+  if (rc != CP_OK || !launch) return rc;
+  const cp_shape& s = *shape;
   const size_t need = decode_workspace_bytes(s);
   if (need > 0 && (workspace == nullptr || !aligned256(workspace) || workspace_bytes < need))
     return CP_ERR_WORKSPACE;
   const float scale = resolve_scale(s.softmax_scale, s.head_dim);
   return launch_decode(s, scale, q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid, out, lse, out_dtype,
                        workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int cp_attn_decode_static(const cp_shape* shape, const void* q, const void* k, const void* v,
+                          const int32_t* q_pos, const int32_t* kv_pos,
+                          const int32_t* cu_seqlens_kv, const int32_t* bid, void* out, float* lse,
+                          int32_t out_dtype, void* stream) {
+  bool launch = false;
+  const int rc = check_decode(shape, q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid, out, lse,
+                              out_dtype, &launch);
+  if (rc != CP_OK || !launch) return rc;
+  const cp_shape& s = *shape;
+  if (decode_workspace_bytes(s) > CP_STATIC_SCRATCH_BYTES) return CP_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const int rs = static_scratch(&ws);
+  if (rs != CP_OK) return rs;
+  const float scale = resolve_scale(s.softmax_scale, s.head_dim);
+  return launch_decode(s, scale, q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid, out, lse, out_dtype,
+                       ws, CP_STATIC_SCRATCH_BYTES, (hipStream_t)stream);
 }
 
 int cp_attn_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* const* outs,

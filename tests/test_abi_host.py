@@ -210,6 +210,16 @@ def test_decode_validates_before_launching(lib):
     assert dec(_shape(total_q=0)) == 0
 
 
+def test_decode_static_rejects_what_does_not_fit(lib):
+    # 4096 queries x 16 heads x 2+ splits of fp32 partials is far beyond the scratch array
+    shape = B.make_shape(B.CP_BF16, 128, 16, 1, 4096, 4096 * 4096, batch=4096)
+    assert B.cp_workspace_bytes(shape, B.CP_WS_DECODE) > B.CP_STATIC_SCRATCH_BYTES
+    one = ctypes.c_void_p(256)
+    rc = lib.cp_attn_decode_static(ctypes.byref(shape), one, one, one, one, one, one, one, one,
+                                   one, B.CP_FP32, None)
+    assert rc == -4   # CP_ERR_WORKSPACE, before anything is launched
+
+
 def test_merge_validates_before_launching(lib):
     vp = ctypes.c_void_p
 
