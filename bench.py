@@ -32,6 +32,7 @@ sys.path.insert(0, ROOT)
 
 from paper_2411_01783_amd import binding as B  # noqa: E402
 from paper_2411_01783_amd import workloads as W  # noqa: E402
+from bench_support import probes as P  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
@@ -378,7 +379,7 @@ def mfma_rate_probe(iters: int = 20000, reps: int = 3):
     (the second draws more power and settles at a lower clock): context for roofline.frac."""
     n_wg = torch.cuda.get_device_properties(0).multi_processor_count
     sink = torch.empty(n_wg * 512, dtype=torch.float32, device="cuda")
-    n_el = B.CP_PROBE_OPERAND_BYTES // 2
+    n_el = P.OPERAND_BYTES // 2
     out = {}
     for name, ops in (("zeros", torch.zeros(n_el, dtype=torch.bfloat16, device="cuda")),
                       ("normal", W.normal(77, (n_el,), "bf16", "cuda"))):
@@ -386,7 +387,7 @@ def mfma_rate_probe(iters: int = 20000, reps: int = 3):
         for _ in range(reps):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-            flop = B.cp_probe_mfma_rate(ops, iters, n_wg, sink)
+            flop = P.mfma_rate(ops, iters, n_wg, sink)
             e1.record()
             torch.cuda.synchronize()
             best = max(best, flop / (e0.elapsed_time(e1) * 1e-3) / 1e12)
@@ -446,7 +447,7 @@ def hbm_read_probe(nbytes: int, n_buffers: int = 16, reps: int = 5):
 
         def one_pass():
             for b in bufs:
-                B.cp_probe_hbm_read(b, n_wg, sink)
+                P.hbm_read(b, n_wg, sink)
         sec = time_steps(one_pass, reps, 2) / n_buffers
         out["us_by_wg_per_cu"][str(wg_per_cu)] = round(sec * 1e6, 2)
         best = sec if best is None else min(best, sec)
@@ -511,6 +512,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     B.load()
+    P.load()
 
     w = W.WORKLOADS[args.workload]
     st = build_prefill(w)

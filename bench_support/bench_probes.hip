@@ -1,11 +1,23 @@
-// Measurement support: what the matrix pipe sustains on this part for given operand values.
-// A loop of independent bf16 MFMAs on register operands, nothing else: the ceiling any
-// MFMA-bound kernel is measured against next to the published peak. With N(0,1) operands the
-// part draws more power than with zeros and settles at a lower clock.
-#include "cp_common.h"
+// Yardsticks for bench.py (not part of libcp_attn and not a step of the paper's method):
+//   bench_probe_mfma_rate  what the matrix pipe sustains on this part for given operand
+//                          values: a loop of independent bf16 MFMAs on register operands and
+//                          nothing else. With N(0,1) operands the part draws more power than
+//                          with zeros and settles at a lower clock.
+//   bench_probe_hbm_read   what one launch that only streams a buffer once achieves, launch
+//                          ramp and tail included: the yardstick for the split-KV decode kernel
+//                          beside the published HBM peak.
+// Both return 0, or a negative value for bad arguments (-1 null pointer, -2 bad size,
+// -5 launch failure, -6 misaligned buffer); work is enqueued on `hip_stream`.
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
 
-namespace cp {
+#define BENCH_PROBE_OPERAND_BYTES 65536
+
 namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx16_t __attribute__((ext_vector_type(16)));
 
 __global__ __launch_bounds__(512) void mfma_rate_probe_kernel(const bf16x8_t* __restrict__ in,
                                                               float* __restrict__ sink,
@@ -43,10 +55,7 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4* __rest
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;
   int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   uint32_t acc = 0;
-#ifndef CP_PROBE_DEPTH
-#define CP_PROBE_DEPTH 8
-#endif
-  constexpr int DEPTH = CP_PROBE_DEPTH;
+  constexpr int DEPTH = 8;
   for (; i + (DEPTH - 1) * stride < n_chunks; i += DEPTH * stride) {
     uint4 t[DEPTH];
 #pragma unroll
@@ -66,28 +75,27 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4* __rest
 }
 
 }  // namespace
-}  // namespace cp
 
-extern "C" int cp_probe_mfma_rate(const void* operands, int32_t iters, int32_t n_workgroups,
+extern "C" int bench_probe_mfma_rate(const void* operands, int32_t iters, int32_t n_workgroups,
                                   void* sink, double* flop_out, void* hip_stream) {
-  static_assert(CP_PROBE_OPERAND_BYTES == 512 * 8 * sizeof(cp::bf16x8_t), "operand block");
-  if (operands == nullptr || sink == nullptr || flop_out == nullptr) return CP_ERR_NULL;
-  if (iters < 1 || n_workgroups < 1) return CP_ERR_SHAPE;
-  hipLaunchKernelGGL(cp::mfma_rate_probe_kernel, dim3(n_workgroups), dim3(512), 0,
-                     (hipStream_t)hip_stream, (const cp::bf16x8_t*)operands, (float*)sink, iters);
-  if (cp::check_launch() != CP_OK) return CP_ERR_LAUNCH;
+  static_assert(BENCH_PROBE_OPERAND_BYTES == 512 * 8 * sizeof(bf16x8_t), "operand block");
+  if (operands == nullptr || sink == nullptr || flop_out == nullptr) return -1;
+  if (iters < 1 || n_workgroups < 1) return -2;
+  hipLaunchKernelGGL(mfma_rate_probe_kernel, dim3(n_workgroups), dim3(512), 0,
+                     (hipStream_t)hip_stream, (const bf16x8_t*)operands, (float*)sink, iters);
+  if (hipGetLastError() != hipSuccess) return -5;
   // 8 wavefronts x 16 MFMAs per iteration, 2 * 32 * 32 * 16 operations each
   *flop_out = (double)n_workgroups * 8.0 * (double)iters * 16.0 * 32768.0;
-  return CP_OK;
+  return 0;
 }
 
-extern "C" int cp_probe_hbm_read(const void* buffer, size_t bytes, int32_t n_workgroups,
+extern "C" int bench_probe_hbm_read(const void* buffer, size_t bytes, int32_t n_workgroups,
                                  void* sink, void* hip_stream) {
-  if (buffer == nullptr || sink == nullptr) return CP_ERR_NULL;
-  if (n_workgroups < 1 || bytes < 16 || bytes % 16 != 0) return CP_ERR_SHAPE;
-  if (((uintptr_t)buffer & 15u) != 0) return CP_ERR_ALIGN;
-  hipLaunchKernelGGL(cp::hbm_read_probe_kernel, dim3(n_workgroups), dim3(256), 0,
+  if (buffer == nullptr || sink == nullptr) return -1;
+  if (n_workgroups < 1 || bytes < 16 || bytes % 16 != 0) return -2;
+  if (((uintptr_t)buffer & 15u) != 0) return -6;
+  hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(n_workgroups), dim3(256), 0,
                      (hipStream_t)hip_stream, (const uint4*)buffer, (int64_t)(bytes / 16),
                      (uint32_t*)sink);
-  return cp::check_launch();
+  return hipGetLastError() == hipSuccess ? 0 : -5;
 }

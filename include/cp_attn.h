@@ -470,33 +470,6 @@ int cp_kv_append(const cp_shape* shape, const void* k_new, const void* v_new,
  */
 int32_t cp_decode_owner(int32_t seq, int32_t decode_iter, int32_t n_ranks);
 
-/*
- * Measurement support (not a step of the paper's method): sustained rate of the matrix
- * pipe. Launches one workgroup of 8 wavefronts per entry of `n_workgroups`, each issuing
- * iters * 16 independent v_mfma_f32_32x32x16_bf16 on the operands found in
- * `operands` (device, at least CP_PROBE_OPERAND_BYTES bytes of bf16, read once into
- * registers), and writes one float per thread to `sink` (device, n_workgroups * 512
- * floats). *flop_out (host) receives the floating-point operations of the launch. The
- * rate depends on the operand VALUES (zeros versus random data draw different power),
- * which is why the caller supplies them. Asynchronous on hip_stream.
- * Errors: CP_ERR_NULL, CP_ERR_SHAPE (iters < 1 or n_workgroups < 1), CP_ERR_LAUNCH.
- */
-#define CP_PROBE_OPERAND_BYTES 65536
-int cp_probe_mfma_rate(const void* operands, int32_t iters, int32_t n_workgroups, void* sink,
-                       double* flop_out, void* hip_stream);
-
-/*
- * Measurement support (not a step of the paper's method): one launch of n_workgroups
- * workgroups of 256 threads that reads `bytes` bytes (a multiple of 16) of `buffer` (device,
- * 16-byte aligned) exactly once with non-temporal 16-byte loads and writes one word per
- * thread to `sink` (device, n_workgroups * 256 words). Its duration is what a single launch
- * that only streams that many bytes achieves on this part, launch ramp and tail included:
- * the yardstick for the split-KV decode kernel beside the published HBM peak.
- * Asynchronous on hip_stream. Errors: CP_ERR_NULL, CP_ERR_SHAPE, CP_ERR_ALIGN, CP_ERR_LAUNCH.
- */
-int cp_probe_hbm_read(const void* buffer, size_t bytes, int32_t n_workgroups, void* sink,
-                      void* hip_stream);
-
 /* Static description of a cp_status. Never NULL. */
 const char* cp_strerror(int status);
 

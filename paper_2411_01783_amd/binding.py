@@ -27,10 +27,9 @@ EXPORTS = [
     "cp_attn_decode", "cp_attn_decode_static",
     "cp_attn_merge", "cp_ring_passkv", "cp_ring_passq", "cp_ring_passq_decode",
     "cp_ring_workspace_bytes", "cp_ring_message_bytes", "cp_ring_prefill", "cp_select_order", "cp_kv_cache_reset", "cp_kv_append",
-    "cp_decode_owner", "cp_probe_mfma_rate", "cp_probe_hbm_read", "cp_strerror",
+    "cp_decode_owner", "cp_strerror",
     "cp_version",
 ]
-CP_PROBE_OPERAND_BYTES = 65536
 CP_STATIC_SCRATCH_BYTES = 8 << 20
 
 _vp = ctypes.c_void_p
@@ -134,10 +133,6 @@ def load() -> ctypes.CDLL:
     lib.cp_kv_append.argtypes = [ctypes.POINTER(cp_shape)] + [_vp] * 11
     lib.cp_decode_owner.restype = _i32
     lib.cp_decode_owner.argtypes = [_i32, _i32, _i32]
-    lib.cp_probe_hbm_read.restype = ctypes.c_int
-    lib.cp_probe_hbm_read.argtypes = [_vp, ctypes.c_size_t, _i32, _vp, _vp]
-    lib.cp_probe_mfma_rate.restype = ctypes.c_int
-    lib.cp_probe_mfma_rate.argtypes = [_vp, _i32, _i32, _vp, ctypes.POINTER(ctypes.c_double), _vp]
     _lib = lib
     return lib
 
@@ -186,28 +181,6 @@ def make_shape(dtype: int, head_dim: int, n_q_heads: int, n_kv_heads: int, total
 
 def cp_version() -> int:
     return int(load().cp_version())
-
-
-def cp_probe_mfma_rate(operands: torch.Tensor, iters: int, n_workgroups: int,
-                       sink: torch.Tensor, stream=None) -> float:
-    """Launch the matrix-pipe rate probe; returns the launch's floating-point operations."""
-    assert operands.numel() * operands.element_size() >= CP_PROBE_OPERAND_BYTES
-    assert sink.numel() >= n_workgroups * 512 and sink.dtype == torch.float32
-    flop = ctypes.c_double(0.0)
-    _check(load().cp_probe_mfma_rate(_ptr(operands), int(iters), int(n_workgroups), _ptr(sink),
-                                     ctypes.byref(flop), _stream(stream)), "cp_probe_mfma_rate")
-    return flop.value
-
-
-def cp_probe_hbm_read(buffer: torch.Tensor, n_workgroups: int, sink: torch.Tensor,
-                      stream=None) -> int:
-    """One streaming read of the whole buffer; returns the bytes read."""
-    nbytes = buffer.numel() * buffer.element_size()
-    if sink.numel() * sink.element_size() < n_workgroups * 256 * 4:
-        raise ValueError("sink too small")
-    _check(load().cp_probe_hbm_read(_ptr(buffer), nbytes, n_workgroups, _ptr(sink),
-                                    _stream(stream)), "cp_probe_hbm_read")
-    return nbytes
 
 
 def cp_shard_positions(total: int, n_ranks: int, rank: int, offset: int = 0) -> np.ndarray:

@@ -72,16 +72,9 @@ __device__ __forceinline__ void wave_lds_sync() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-#ifdef CP_DEC_STAMPS
-__device__ unsigned long long cp_dec_dbg[4096 * 8];
-#define DEC_STAMP(i) do { if ((threadIdx.x & 63) == 0) cp_dec_dbg[((blockIdx.y * gridDim.x + blockIdx.x) * NWAVE + (threadIdx.x >> 6)) * 8 + (i)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define DEC_STAMP(i) do { } while (0)
-#endif
 
 __global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
   extern __shared__ __align__(16) char smem[];
-  DEC_STAMP(0);
   const int tid = threadIdx.x;
   const int wave = tid >> 6, lane = tid & 63;
   const int hd = lane & 15;   // query head within the group (N side)
@@ -200,17 +193,13 @@ __global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
   };
 
   int64_t key0 = c0 + (int64_t)wave * TILE;
-  DEC_STAMP(1);
   if (key0 < c1) load_tile(key0);
-  int n_tiles_done = 0;
 
   while (key0 < c1) {
     // positions of the 8 keys whose scores this lane holds (block kb, key kg*4 + i)
     const int32_t kp[8] = {r.p0, r.p1, r.p2, r.p3, r.p4, r.p5, r.p6, r.p7};
     wave_lds_sync();  // previous tile's LDS reads are done before it is overwritten
     store_tile();
-    if (n_tiles_done == 0) DEC_STAMP(2);
-    ++n_tiles_done;
     const int64_t key_next = key0 + NWAVE * TILE;
     if (key_next < c1) load_tile(key_next);
     wave_lds_sync();
@@ -265,10 +254,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
     key0 = key_next;
   }
 
-  DEC_STAMP(3);
-#ifdef CP_DEC_STAMPS
-  if ((threadIdx.x & 63) == 0) cp_dec_dbg[((blockIdx.y * gridDim.x + blockIdx.x) * NWAVE + (threadIdx.x >> 6)) * 8 + 6] = n_tiles_done;
-#endif
   // ---- combine the four wavefronts (disjoint key subsets) in LDS ----
   l_run += __shfl_xor(l_run, 16, 64);
   l_run += __shfl_xor(l_run, 32, 64);
@@ -328,7 +313,6 @@ __global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
         p.part_lse[prow] = den > 0.f ? (mmax + __builtin_amdgcn_logf(den)) * kLn2 : -INFINITY;
     }
   }
-  DEC_STAMP(4);
 }
 
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -389,8 +373,3 @@ int launch_decode(const cp_shape& s, float scale, const void* q, const void* k, 
 
 }  // namespace cp
 
-#ifdef CP_DEC_STAMPS
-extern "C" int cp_dec_debug_read(void* dst) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(cp::cp_dec_dbg), sizeof(cp::cp_dec_dbg));
-}
-#endif

@@ -48,10 +48,7 @@ constexpr int MAX_LIVE = 512;   // live-tile list entries per chunk (8 wavefront
 constexpr int OUT_STRIDE = D * 4 + 16;    // epilogue staging: one fp32 output row + pad
 constexpr float kRescaleSlack = 8.f;               // log2 units
 constexpr float kOverflowSum = 1099511627776.f;    // 2^40: a block sum beyond it is redone
-#ifndef CP_MIN_TILES_PER_SPLIT
-#define CP_MIN_TILES_PER_SPLIT 1
-#endif
-constexpr int kMinTilesPerSplit = CP_MIN_TILES_PER_SPLIT;
+constexpr int kMinTilesPerSplit = 1;
 
 struct Params {
   const bf16_t* q;
@@ -337,11 +334,3 @@ int launch_prefill_mfma_ring(const cp_shape& s, float scale, const void* q, cons
 
 }  // namespace cp
 
-#ifdef CP_PIPE_STAMPS
-extern "C" int cp_debug_read(void* dst) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(cp::cp_dbg), sizeof(cp::cp_dbg));
-}
-extern "C" int cp_debug_read2(void* dst) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(cp::cp_dbg2), sizeof(cp::cp_dbg2));
-}
-#endif

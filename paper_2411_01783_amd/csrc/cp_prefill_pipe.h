@@ -116,13 +116,6 @@ struct PipeRegs {
   float m_run, l_run;
 };
 
-#ifdef CP_PIPE_STAMPS
-__device__ unsigned long long cp_dbg[1024 * 8 * 8];
-__device__ unsigned long long cp_dbg2[1024 * 8 * 8];
-#define CP_STAMP(i) do { const unsigned long long t_ = __builtin_readcyclecounter(); st[i] += t_ - t_prev; t_prev = t_; } while (0)
-#else
-#define CP_STAMP(i) do { } while (0)
-#endif
 
 template <int J>
 struct IntC {
@@ -391,10 +384,6 @@ __device__ __forceinline__ void prefill_body(const Params& p,
   int4* const live = (int4*)(smem + OFF_LIVE8);
   const uint32_t smem_lds = (uint32_t)(size_t)(CP_LDS_AS char*)smem;
 
-#ifdef CP_PIPE_STAMPS
-  const unsigned long long t_entry = __builtin_readcyclecounter();
-  unsigned long long t_loop0 = t_entry, t_loop1 = t_entry, t_p1 = t_entry, t_p2 = t_entry, t_p3 = t_entry;
-#endif
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int n = lane & 31, g = lane >> 5;
@@ -454,9 +443,6 @@ __device__ __forceinline__ void prefill_body(const Params& p,
     if (BAND) wg_scratch[NWAVE + 1 + wave] = w_lomin;
   }
   lds_barrier();
-#ifdef CP_PIPE_STAMPS
-  t_p1 = __builtin_readcyclecounter();
-#endif
   int wg_qmax = INT32_MIN, wg_lomin = INT32_MAX;
 #pragma unroll
   for (int w = 0; w < NWAVE; ++w) {
@@ -568,9 +554,6 @@ __device__ __forceinline__ void prefill_body(const Params& p,
       lds_barrier();
       const int n_live = __builtin_amdgcn_readfirstlane(wg_scratch[NWAVE]);
       if (n_live == 0) continue;
-#ifdef CP_PIPE_STAMPS
-      t_p2 = __builtin_readcyclecounter();
-#endif
 
       // ---- prologue: tile 0 into buffer 0, Q stage of block 0 ----
       int32_t next_pos = 0;
@@ -594,9 +577,6 @@ __device__ __forceinline__ void prefill_body(const Params& p,
         const int32_t pos = load_pos(key0);
         if (tid < TILE) posbuf0[tid] = pos;
         __syncthreads();  // waits for the tile (vmcnt) and publishes it
-#ifdef CP_PIPE_STAMPS
-        t_p3 = __builtin_readcyclecounter();
-#endif
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) R.kf[ks] = lds_read_b128<0>(kaddr[ks]);
         lgkm_wait<0>(R.kf[0], R.kf[1], R.kf[2], R.kf[3]);
@@ -616,15 +596,9 @@ __device__ __forceinline__ void prefill_body(const Params& p,
       }
 
       auto no_hook = [](auto) {};
-#ifdef CP_PIPE_STAMPS
-      unsigned long long st[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-      unsigned long long t_prev = __builtin_readcyclecounter();
-      t_loop0 = t_prev;
-#endif
       for (int it = 0; it < n_live; ++it) {
         const bool has_next = it + 1 < n_live;
         const int nb = (it + 1) & 1;
-        CP_STAMP(5);
         // The next tile is requested during the first two steps, one part (a K and a V
         // instruction per wavefront) at a time: a burst of all eight fills the memory pipeline's
         // queue and stalls every wavefront behind it.
@@ -645,23 +619,18 @@ __device__ __forceinline__ void prefill_body(const Params& p,
                            });
         pipe_body<2, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, need_mask, have_ref, no_hook);
         // barrier Y: the next tile has landed in every wavefront
-        CP_STAMP(0);
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        CP_STAMP(1);
         if (has_next && tid < TILE) posbuf0[nb * TILE + tid] = next_pos;
         const bool cur_mask = need_mask;
         need_mask = next_mask;
         read_entry(it + 2, next_key0, next_mask);  // no direct-to-LDS load is in flight here
         __syncthreads();
-        CP_STAMP(2);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) kaddr[ks] ^= KD_BYTES;  // K of the next tile from here on
         pipe_body<3, BAND>(R, qf, kaddr, vaddr, paddr, qp, ql, scale_log2, cur_mask, have_ref, no_hook);
         // barrier X: every LDS read of this tile has completed; its buffers may be refilled
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
-        CP_STAMP(3);
         __syncthreads();
-        CP_STAMP(4);
 #pragma unroll
         for (int db = 0; db < 4; ++db) vaddr[db] ^= KD_BYTES;
         paddr ^= POS_BYTES;
@@ -679,11 +648,6 @@ __device__ __forceinline__ void prefill_body(const Params& p,
         last(IntC<4>{}); last(IntC<5>{}); last(IntC<6>{}); last(IntC<7>{});
         __builtin_amdgcn_sched_barrier(0);
       }
-#ifdef CP_PIPE_STAMPS
-      if (lane == 0 && split == 0 && kvh == 0 && blockIdx.x < 1024)
-        for (int i = 0; i < 8; ++i) cp_dbg[(blockIdx.x * 8 + wave) * 8 + i] = i == 7 ? (unsigned long long)n_live : st[i];
-      t_loop1 = __builtin_readcyclecounter();
-#endif
       // back to buffer-0 addressing for the next chunk
       if (n_live & 1) {
 #pragma unroll
@@ -813,14 +777,6 @@ __device__ __forceinline__ void prefill_body(const Params& p,
       if (r0 + rr < p.rows) *(floatx4_t*)(o + rl * D + c) = a;
     }
   }
-#ifdef CP_PIPE_STAMPS
-  if (lane == 0 && split == 0 && kvh == 0 && blockIdx.x < 1024) {
-    const unsigned long long t_end = __builtin_readcyclecounter();
-    unsigned long long* d2 = cp_dbg2 + (blockIdx.x * 8 + wave) * 8;
-    d2[0] = t_loop0 - t_entry; d2[1] = t_loop1 - t_loop0; d2[2] = t_end - t_loop1; d2[3] = t_entry;
-    d2[4] = t_p1 - t_entry; d2[5] = t_p2 - t_p1; d2[6] = t_p3 - t_p2; d2[7] = t_loop0 - t_p3;
-  }
-#endif
 }
 
 template <typename TO, bool BAND, bool SPLIT, bool ACC = false>

@@ -46,17 +46,6 @@ def test_partial_accumulate_rejects_what_it_cannot_run(lib):
                                           None, 0, None, one, ctypes.c_size_t(1 << 30), None) == -1
 
 
-def test_probe_rejects_bad_arguments_before_any_launch(lib):
-    import ctypes
-    flop = ctypes.c_double(0.0)
-    one = ctypes.c_void_p(256)  # never dereferenced: every call below fails validation first
-    assert lib.cp_probe_mfma_rate(None, 1, 1, one, ctypes.byref(flop), None) == -1  # CP_ERR_NULL
-    assert lib.cp_probe_mfma_rate(one, 1, 1, None, ctypes.byref(flop), None) == -1
-    assert lib.cp_probe_mfma_rate(one, 1, 1, one, None, None) == -1
-    assert lib.cp_probe_mfma_rate(one, 0, 1, one, ctypes.byref(flop), None) == -2  # CP_ERR_SHAPE
-    assert lib.cp_probe_mfma_rate(one, 1, 0, one, ctypes.byref(flop), None) == -2
-
-
 def test_kv_cache_calls_validate_before_launching(lib):
     one = ctypes.c_void_p(256)    # never dereferenced: every call below fails validation first
     odd = ctypes.c_void_p(264)    # not 16-byte aligned
@@ -93,16 +82,6 @@ def test_decode_owner_matches_oracle(lib, oracle):
                 assert lib.cp_decode_owner(b, t, n) == oracle.decode_owner(b, t, n)
     assert lib.cp_decode_owner(0, 0, 0) == -2
     assert lib.cp_decode_owner(-1, 0, 4) == -2
-
-
-def test_hbm_probe_rejects_bad_arguments_before_any_launch(lib):
-    one = ctypes.c_void_p(256)  # never dereferenced: every call below fails validation first
-    assert lib.cp_probe_hbm_read(None, ctypes.c_size_t(1024), 1, one, None) == -1
-    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(1024), 1, None, None) == -1
-    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(1000), 1, one, None) == -2
-    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(0), 1, one, None) == -2
-    assert lib.cp_probe_hbm_read(one, ctypes.c_size_t(1024), 0, one, None) == -2
-    assert lib.cp_probe_hbm_read(ctypes.c_void_p(260), ctypes.c_size_t(1024), 1, one, None) == -6
 
 
 def test_ring_prefill_validates_before_launching(lib):
@@ -364,3 +343,18 @@ def test_ctypes_structs_match_the_header_layout(tmp_path):
         assert int(got[name]) == ctypes.sizeof(cls), name
         for field, _ in cls._fields_:
             assert int(got["%s.%s" % (name, field)]) == getattr(cls, field).offset, (name, field)
+
+
+def test_bench_probe_library_builds_and_validates():
+    """bench.py's yardstick kernels live in a library of their own, outside the C ABI."""
+    from bench_support import probes
+    probes.build()
+    lib = probes.load()
+    flop = ctypes.c_double(0.0)
+    one = ctypes.c_void_p(256)  # never dereferenced: every call below fails validation first
+    assert lib.bench_probe_mfma_rate(None, 1, 1, one, ctypes.byref(flop), None) == -1
+    assert lib.bench_probe_mfma_rate(one, 0, 1, one, ctypes.byref(flop), None) == -2
+    assert lib.bench_probe_hbm_read(None, ctypes.c_size_t(1024), 1, one, None) == -1
+    assert lib.bench_probe_hbm_read(one, ctypes.c_size_t(1000), 1, one, None) == -2
+    assert lib.bench_probe_hbm_read(ctypes.c_void_p(260), ctypes.c_size_t(1024), 1, one, None) == -6
+    assert not hasattr(B.load(), "cp_probe_mfma_rate")
