@@ -65,6 +65,15 @@ typedef enum {
   CP_WS_MERGE = 2    /* cp_attn_merge (needs none; returns 0) */
 } cp_ws_kind;
 
+/*
+ * cp_shape.flags. CP_SHAPE_UNIQUE_BID (cp_attn_decode, cp_attn_decode_static): the caller
+ * promises that no sequence id occurs twice in `bid`, as in Algorithm 4, where every sequence
+ * has exactly one new token. The call may then take a faster path that reads the rank's whole
+ * packed KV in equal ranges per workgroup. If the promise is broken, the queries that share a
+ * sequence get unspecified results (all accesses stay in bounds). Ignored by other calls.
+ */
+#define CP_SHAPE_UNIQUE_BID 1
+
 /* Problem shape of one attention call. */
 typedef struct {
   int32_t dtype;      /* cp_dtype of Q, K, V */
@@ -72,7 +81,7 @@ typedef struct {
   int32_t n_q_heads;  /* N_H  on this GPU */
   int32_t n_kv_heads; /* N_KV on this GPU; divides n_q_heads */
   int32_t batch;      /* number of packed sequences; 1 when cu_seqlens are NULL */
-  int32_t reserved;   /* must be 0 */
+  int32_t flags;      /* 0, or CP_SHAPE_* bits */
   int64_t total_q;    /* packed query tokens  (>= 0) */
   int64_t total_kv;   /* packed KV tokens     (>= 0) */
   float softmax_scale; /* <= 0 selects 1/sqrt(head_dim) (Appendix B) */
@@ -335,6 +344,16 @@ typedef struct {
    * fused_merge, gathered_q or aux_stream.
    */
   const int32_t* const* cu_seqlens_q;
+  /*
+   * cp_ring_passq_decode only. 1: the caller promises that the bid arrays of all ranks
+   * together name every sequence at most once (Algorithm 4: one new token per sequence), and
+   * every decode call is made with CP_SHAPE_UNIQUE_BID. With gathered_q, each KV holder then
+   * writes its split-KV partials into its own part of the workspace and ONE launch applies
+   * Equation 4 over splits and holders together (the merge is associative, and Algorithm 4
+   * merges once, after the All2All); the partial slots partial_out / partial_lse are then not
+   * written. 0: no promise.
+   */
+  int32_t unique_bid;
 } cp_ring_desc;
 
 /* Bytes of one message of message_layout 1 (see cp_ring_desc); 0 for an invalid descriptor.

@@ -21,6 +21,7 @@ CP_WS_PARTIAL, CP_WS_DECODE, CP_WS_MERGE = 0, 1, 2
 CP_POS_PAD_KV = 2**31 - 1
 CP_POS_PAD_Q = -1
 CP_MAX_PARTS = 64
+CP_SHAPE_UNIQUE_BID = 1
 
 EXPORTS = [
     "cp_shard_positions", "cp_workspace_bytes", "cp_attn_partial", "cp_attn_partial_accumulate",
@@ -38,7 +39,7 @@ _i32, _i64, _f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
 
 class cp_shape(ctypes.Structure):
     _fields_ = [("dtype", _i32), ("head_dim", _i32), ("n_q_heads", _i32), ("n_kv_heads", _i32),
-                ("batch", _i32), ("reserved", _i32), ("total_q", _i64), ("total_kv", _i64),
+                ("batch", _i32), ("flags", _i32), ("total_q", _i64), ("total_kv", _i64),
                 ("softmax_scale", _f32), ("reserved_f", _f32)]
 
 
@@ -57,7 +58,8 @@ class cp_ring_desc(ctypes.Structure):
                 ("cu_seqlens_kv", ctypes.POINTER(_vp)), ("bid", ctypes.POINTER(_vp)),
                 ("aux_stream", _vp), ("message_layout", _i32),
                 ("arrived", ctypes.POINTER(_vp)), ("ring_error", _vp), ("spin_limit", _i32),
-                ("gathered_q", _i32), ("cu_seqlens_q", ctypes.POINTER(_vp))]
+                ("gathered_q", _i32), ("cu_seqlens_q", ctypes.POINTER(_vp)),
+                ("unique_bid", _i32)]
 
 
 class cp_select_params(ctypes.Structure):
@@ -172,8 +174,9 @@ def _stream(stream) -> Optional[int]:
 
 
 def make_shape(dtype: int, head_dim: int, n_q_heads: int, n_kv_heads: int, total_q: int,
-               total_kv: int, batch: int = 1, softmax_scale: float = 0.0) -> cp_shape:
-    return cp_shape(dtype, head_dim, n_q_heads, n_kv_heads, batch, 0, total_q, total_kv,
+               total_kv: int, batch: int = 1, softmax_scale: float = 0.0,
+               flags: int = 0) -> cp_shape:
+    return cp_shape(dtype, head_dim, n_q_heads, n_kv_heads, batch, flags, total_q, total_kv,
                     softmax_scale, 0.0)
 
 
@@ -272,13 +275,15 @@ def cp_attn_partial_accumulate(q, k, v, q_pos, kv_pos, acc_out, acc_lse, final_o
 
 def cp_attn_decode(q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid,
                    out_dtype: Optional[torch.dtype] = None, softmax_scale: float = 0.0,
-                   out=None, lse=None, workspace=None, stream=None):
-    """Decode step: query i attends to KV segment bid[i] of the packed k, v."""
+                   out=None, lse=None, workspace=None, stream=None, unique_bid: bool = False):
+    """Decode step: query i attends to KV segment bid[i] of the packed k, v. `unique_bid`:
+    the caller's promise that no sequence id occurs twice (CP_SHAPE_UNIQUE_BID)."""
     lib = load()
     nq, nh, d = q.shape
     tkv, nkv, _ = k.shape
     batch = cu_seqlens_kv.numel() - 1
-    shape = make_shape(dtype_code(q.dtype), d, nh, nkv, nq, tkv, batch, softmax_scale)
+    shape = make_shape(dtype_code(q.dtype), d, nh, nkv, nq, tkv, batch, softmax_scale,
+                       CP_SHAPE_UNIQUE_BID if unique_bid else 0)
     odt = q.dtype if out_dtype is None else out_dtype
     if out is None:
         out = torch.empty((nq, nh, d), dtype=odt, device=q.device)
@@ -295,13 +300,13 @@ def cp_attn_decode(q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid,
 
 
 def cp_attn_decode_static(q, k, v, q_pos, kv_pos, cu_seqlens_kv, bid, out, lse,
-                          softmax_scale: float = 0.0, stream=None):
+                          softmax_scale: float = 0.0, stream=None, unique_bid: bool = False):
     """cp_attn_decode into caller-provided `out` / `lse`, with the library's own scratch array
     in place of a workspace: the call allocates nothing (nor does this wrapper)."""
     nq, nh, d = q.shape
     tkv, nkv, _ = k.shape
     shape = make_shape(dtype_code(q.dtype), d, nh, nkv, nq, tkv, cu_seqlens_kv.numel() - 1,
-                       softmax_scale)
+                       softmax_scale, CP_SHAPE_UNIQUE_BID if unique_bid else 0)
     _check(load().cp_attn_decode_static(ctypes.byref(shape), _ptr(q), _ptr(k), _ptr(v),
                                         _ptr(q_pos), _ptr(kv_pos), _ptr(cu_seqlens_kv), _ptr(bid),
                                         _ptr(out), _ptr(lse), dtype_code(out.dtype),
@@ -391,7 +396,7 @@ class Ring:
                  fused_merge=False, message_layout: bool = False,
                  arrived: Optional[List[torch.Tensor]] = None, spin_limit: int = 1 << 16,
                  gathered_q: bool = False,
-                 cu_seqlens_q: Optional[List[torch.Tensor]] = None):
+                 cu_seqlens_q: Optional[List[torch.Tensor]] = None, unique_bid: bool = False):
         n = len(q)
         self.n = n
         self.decode = cu_seqlens_kv is not None and cu_seqlens_q is None
@@ -449,6 +454,7 @@ class Ring:
         dsc.keep_partials = 1 if keep_partials else 0
         dsc.fused_merge = int(fused_merge)   # False/True, or 2: all steps of a rank in one launch
         dsc.gathered_q = 1 if gathered_q else 0
+        dsc.unique_bid = 1 if unique_bid else 0
         self.gathered = gathered_q
         self.arrived = arrived
         if arrived is not None:

@@ -22,7 +22,7 @@ int check_shape(const cp_shape* s) {
     return CP_ERR_SHAPE;
   if (s->batch < 1 || s->total_q < 0 || s->total_kv < 0) return CP_ERR_SHAPE;
   if (s->total_q > 0x7fffffffLL || s->total_kv > 0x7fffffffLL) return CP_ERR_SHAPE;
-  if (s->reserved != 0 || s->reserved_f != 0.f) return CP_ERR_SHAPE;
+  if ((s->flags & ~CP_SHAPE_UNIQUE_BID) != 0 || s->reserved_f != 0.f) return CP_ERR_SHAPE;
   if (!(s->softmax_scale == s->softmax_scale) || isinf(s->softmax_scale)) return CP_ERR_SHAPE;
   return CP_OK;
 }
@@ -293,6 +293,7 @@ static int check_ring(const cp_ring_desc* d, bool decode) {
   if (d->fused_merge < 0 || d->fused_merge > 2) return CP_ERR_SHAPE;
   if (d->message_layout != 0 && d->message_layout != 1) return CP_ERR_SHAPE;
   if (d->gathered_q != 0 && d->gathered_q != 1) return CP_ERR_SHAPE;
+  if (d->unique_bid != 0 && d->unique_bid != 1) return CP_ERR_SHAPE;
   if (d->gathered_q && (!d->keep_partials || d->message_layout || d->fused_merge))
     return CP_ERR_UNSUPPORTED;
   if (d->fused_merge && (decode || d->keep_partials || d->part_dtype != CP_FP32))
@@ -343,6 +344,7 @@ static cp_shape ring_shape(const cp_ring_desc* d, int q_rank, int kv_rank, bool 
   s.n_kv_heads = d->n_kv_heads; s.batch = (decode || ring_is_packed(d, decode)) ? d->batch : 1;
   s.total_q = d->n_q[q_rank]; s.total_kv = d->n_kv[kv_rank];
   s.softmax_scale = d->softmax_scale;
+  if (decode && d->unique_bid) s.flags = CP_SHAPE_UNIQUE_BID;
   return s;
 }
 
@@ -361,6 +363,14 @@ static size_t ring_bounds_bytes(const cp_ring_desc* d, bool decode) {
   return total;
 }
 
+// Shape of the one decode call KV holder b answers with when the queries are gathered.
+static cp_shape gathered_decode_shape(const cp_ring_desc* d, int b) {
+  cp_shape s = ring_shape(d, 0, b, true);
+  s.total_q = 0;
+  for (int a = 0; a < d->n_ranks; ++a) s.total_q += d->n_q[a];
+  return s;
+}
+
 extern "C" size_t cp_ring_workspace_bytes(const cp_ring_desc* d, int32_t decode) {
   if (check_ring(d, decode != 0) != CP_OK) return 0;
   size_t need = 0;
@@ -375,6 +385,16 @@ extern "C" size_t cp_ring_workspace_bytes(const cp_ring_desc* d, int32_t decode)
       s.total_q = 0;
       for (int a = 0; a < d->n_ranks; ++a) s.total_q += d->n_q[a];
       need = std::max(need, cp_workspace_bytes(&s, decode ? CP_WS_DECODE : CP_WS_PARTIAL));
+    }
+    if (decode) {
+      size_t regions = 0;
+      bool flat = true;
+      for (int b = 0; b < d->n_ranks; ++b) {
+        const cp_shape s = gathered_decode_shape(d, b);
+        flat = flat && decode_flat_applies(s);
+        regions += decode_flat_region_bytes(s);
+      }
+      if (flat) need = std::max(need, regions);
     }
   }
   return need + ring_bounds_bytes(d, decode != 0);
@@ -655,6 +675,48 @@ static int ring_passq_gathered(const cp_ring_desc* d, bool decode, hipStream_t s
   RingWork w;
   int rc = ring_prepare(d, decode, st, w);
   if (rc != CP_OK) return rc;
+  if (decode) {
+    // Every holder's split-KV partials into its own region, one merge over splits x holders.
+    cp_shape shapes[CP_MAX_PARTS];
+    void* regions[CP_MAX_PARTS];
+    bool flat = true;
+    size_t off = 0;
+    for (int k = 0; k < n; ++k) {
+      shapes[k] = gathered_decode_shape(d, k);
+      flat = flat && decode_flat_applies(shapes[k]);
+      regions[k] = w.call_ws + off;
+      off += decode_flat_region_bytes(shapes[k]);
+    }
+    if (flat) {
+      if (off > w.call_ws_bytes) return CP_ERR_WORKSPACE;
+      for (int k = 0; k < n && rc == CP_OK; ++k) {
+        if (!aligned16(d->q[0]) || !aligned16(d->k[k]) || !aligned16(d->v[k])) rc = CP_ERR_ALIGN;
+        else
+          rc = launch_decode_flat_partials(
+              shapes[k], resolve_scale(d->softmax_scale, d->head_dim), d->q[0], d->k[k], d->v[k],
+              d->q_pos[0], d->kv_pos[k], d->cu_seqlens_kv[k], d->bid[0], regions[k],
+              decode_flat_region_bytes(shapes[k]), st);
+      }
+      if (rc != CP_OK) return rc;
+      const size_t out_row = (size_t)d->n_q_heads * d->head_dim * elem_size(d->out_dtype);
+      bool one = true;
+      for (int a = 1; a < n && one; ++a) {
+        one = (char*)d->out[a] == (char*)d->out[a - 1] + d->n_q[a - 1] * out_row;
+        if (d->lse != nullptr)
+          one = one && d->lse[a] != nullptr && d->lse[0] != nullptr &&
+                d->lse[a] == d->lse[a - 1] + d->n_q[a - 1] * d->n_q_heads;
+      }
+      if (one)
+        return launch_decode_flat_merge(n, shapes, regions, d->cu_seqlens_kv, d->bid[0],
+                                        (int64_t)n * d->n_q[0], d->out[0], d->out_dtype,
+                                        d->lse != nullptr ? d->lse[0] : nullptr, st);
+      for (int a = 0; a < n && rc == CP_OK; ++a)
+        rc = launch_decode_flat_merge(n, shapes, regions, d->cu_seqlens_kv, d->bid[a], d->n_q[a],
+                                      d->out[a], d->out_dtype,
+                                      d->lse != nullptr ? d->lse[a] : nullptr, st);
+      return rc;
+    }
+  }
   for (int k = 0; k < n && rc == CP_OK; ++k) {
     cp_shape s = ring_shape(d, 0, k, decode);
     s.total_q = (int64_t)n * d->n_q[0];

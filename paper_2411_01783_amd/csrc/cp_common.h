@@ -99,6 +99,20 @@ int launch_decode(const cp_shape& s, float scale, const void* q, const void* k, 
                   const int32_t* bid, void* out, float* lse, int32_t out_dtype, void* workspace,
                   size_t workspace_bytes, hipStream_t stream);
 
+// Flat split-KV decode (cp_shape.flags has CP_SHAPE_UNIQUE_BID): the partials of one KV holder
+// go to `region` (decode_flat_region_bytes), and one merge launch applies Equation 4 over the
+// regions of n_holders holders (shapes[k], regions[k], cu_kv[k] describe holder k; all share
+// the queries' bid, n_q and head counts).
+bool decode_flat_applies(const cp_shape& s);
+size_t decode_flat_region_bytes(const cp_shape& s);
+int launch_decode_flat_partials(const cp_shape& s, float scale, const void* q, const void* k,
+                                const void* v, const int32_t* q_pos, const int32_t* kv_pos,
+                                const int32_t* cu_kv, const int32_t* bid, void* region,
+                                size_t region_bytes, hipStream_t stream);
+int launch_decode_flat_merge(int n_holders, const cp_shape* shapes, void* const* regions,
+                             const int32_t* const* cu_kv, const int32_t* bid, int64_t n_q,
+                             void* out, int32_t out_dtype, float* lse, hipStream_t stream);
+
 // Equation 4 over n_parts partials given as device pointers.
 int launch_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* const* outs,
                  const float* const* lses, int32_t part_dtype, void* out, int32_t out_dtype,

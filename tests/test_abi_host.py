@@ -170,7 +170,7 @@ def test_partial_validates_before_launching(lib):
     assert _partial(lib, _shape(), wsn=16) == -4
     assert _partial(lib, _shape(total_q=0)) == 0          # nothing to do, nothing launched
     s = _shape()
-    s.reserved = 1
+    s.flags = 2
     assert _partial(lib, s) == -2
 
 

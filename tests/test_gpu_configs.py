@@ -209,11 +209,26 @@ def test_decode_b32_passq_ring_full(oracle):
                    cu_seqlens_kv=rcu, bid=[bid_g[x] for x in sl])
     gout, glse = B.cp_ring_passq_decode(gring)
     torch.cuda.synchronize()
+    # and with the promise that no sequence has two queries: flat key ranges per holder, one
+    # merge over splits and holders (the launch configuration bench.py times)
+    uring = B.Ring([q_g[x] for x in sl], rk, rv, [qpos_g[x] for x in sl], rpos,
+                   out_dtype=torch.float32, keep_partials=True, gathered_q=True,
+                   cu_seqlens_kv=rcu, bid=[bid_g[x] for x in sl], unique_bid=True)
+    uout, ulse = B.cp_ring_passq_decode(uring)
+    torch.cuda.synchronize()
     for r in range(n):
         # (different split counts for 2 and for 32 queries: same result up to fp32 rounding;
         # the step-by-step outputs are compared with the oracle below)
         assert float((gout[r] - out[r]).abs().max()) < 1e-4
         assert float((glse[r] - lse[r]).abs().max()) < 1e-4
+    for r in range(n):
+        for i, b in enumerate(rbid[r].cpu().numpy()):
+            L = int(lengths[b])
+            ref_o, ref_l = oracle.attn(W.to_f64(qs[b:b + 1]), W.to_f64(ks[b]), W.to_f64(vs[b]),
+                                       [L - 1], np.arange(L))
+            check(uout[r][i:i + 1], ulse[r][i:i + 1], ref_o, ref_l,
+                  what="sequence %d, flat ranges" % b)
+            assert rel_l2(uout[r][i:i + 1], ref_o) < 2e-2
     for r in range(n):
         for i, b in enumerate(rbid[r].cpu().numpy()):
             L = int(lengths[b])
@@ -226,7 +241,10 @@ def test_decode_b32_passq_ring_full(oracle):
     allbid = i32(np.arange(w.batch))
     o1, l1 = B.cp_attn_decode(qs, rk[2], rv[2], allq_pos, rpos[2], rcu[2], allbid,
                               out_dtype=torch.float32)
+    o2, l2 = B.cp_attn_decode(qs, rk[2], rv[2], allq_pos, rpos[2], rcu[2], allbid,
+                              out_dtype=torch.float32, unique_bid=True)
     torch.cuda.synchronize()
+    assert float((o2 - o1).abs().max()) < 1e-4 and float((l2 - l1).abs().max()) < 1e-4
     b = 5
     p = np.concatenate([B.cp_shard_positions(int(lengths[b]) - 1, n, 2),
                         np.array([lengths[b] - 1] if b % n == 2 else [], dtype=np.int32)])

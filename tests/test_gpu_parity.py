@@ -514,7 +514,7 @@ def test_merge_large_stream(oracle):
 # split-KV decode (Algorithm 4)
 # ---------------------------------------------------------------------------
 
-def _decode_case(oracle, lengths, nh, nkv, bid, seed, pad_some=False):
+def _decode_case(oracle, lengths, nh, nkv, bid, seed, pad_some=False, unique_bid=False):
     total = int(np.sum(lengths))
     cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
     nq = len(bid)
@@ -534,9 +534,9 @@ def _decode_case(oracle, lengths, nh, nkv, bid, seed, pad_some=False):
                       cu_q=np.arange(nq + 1, dtype=np.int32), cu_kv=cu_sel)
     for odt in (torch.float32, torch.bfloat16):
         o, l = B.cp_attn_decode(dev(q), dev(k), dev(v), i32(qp), i32(kp), i32(cu), i32(bid),
-                                out_dtype=odt)
+                                out_dtype=odt, unique_bid=unique_bid)
         torch.cuda.synchronize()
-        check(o, l, *ref, what="decode out %s" % odt)
+        check(o, l, *ref, what="decode out %s%s" % (odt, " (flat ranges)" if unique_bid else ""))
 
 
 def test_decode_varied_lengths(oracle):
@@ -550,6 +550,28 @@ def test_decode_subset_of_sequences_permuted(oracle):
 def test_decode_smaller_groups(oracle):
     _decode_case(oracle, [300, 700, 1500], 8, 2, [2, 0, 1], 96)
     _decode_case(oracle, [300, 700], 4, 4, [1, 0], 99)
+
+
+# The flat path (CP_SHAPE_UNIQUE_BID): equal key ranges per workgroup regardless of the sequence
+# boundaries. The cases put boundaries inside ranges and inside tiles, leave sequences without
+# a query, and include empty and one-key sequences.
+@pytest.mark.parametrize("lengths,bid", [
+    ([1000, 1, 33, 4097, 0, 260, 129], [0, 1, 2, 3, 4, 5, 6]),
+    ([500, 900, 64, 2000, 31], [3, 0, 4]),                 # permuted, two sequences unasked
+    ([7, 3, 1, 0, 0, 2, 40, 5, 9, 1], [9, 8, 7, 6, 5, 4, 3, 2, 1, 0]),   # many ends in one tile
+    ([8192 * 3 + 17, 5000, 12345], [2, 1, 0]),             # several tiles per wavefront
+    ([32 * 256], [0]),                                     # ranges end exactly on the sequence
+    ([64] * 64, list(range(63, -1, -1))),                  # a boundary at every range end
+])
+def test_decode_flat_ranges(oracle, lengths, bid):
+    _decode_case(oracle, lengths, 16, 1, bid, 120 + len(lengths), unique_bid=True)
+
+
+def test_decode_flat_ranges_pads_and_groups(oracle):
+    _decode_case(oracle, [500, 900, 64, 2000, 31], 16, 1, [3, 0, 1, 4], 131, pad_some=True,
+                 unique_bid=True)
+    _decode_case(oracle, [300, 700, 1500], 8, 2, [2, 0, 1], 134, unique_bid=True)
+    _decode_case(oracle, [300, 700], 4, 4, [1, 0], 137, unique_bid=True)
 
 
 def test_ring_passq_decode_driver(oracle):
@@ -755,14 +777,19 @@ def test_ring_passq_gathered_queries_decode(oracle):
     qpos_all = i32(np.concatenate([r["q_pos"] for r in ranks]))
     bid_all = i32(np.concatenate([r["bid"] for r in ranks]))
     sl = [slice(s * m, (s + 1) * m) for s in range(n)]
-    ring = B.Ring([q_all[x] for x in sl], [dev(x) for x in rk], [dev(x) for x in rv],
-                  [qpos_all[x] for x in sl], [i32(r["kv_pos"]) for r in ranks],
-                  out_dtype=torch.float32, keep_partials=True, gathered_q=True,
-                  cu_seqlens_kv=[i32(r["cu_kv"]) for r in ranks], bid=[bid_all[x] for x in sl])
-    out, lse = B.cp_ring_passq_decode(ring)
-    torch.cuda.synchronize()
-    for s in range(n):
-        check(out[s], lse[s], ref_o[s], ref_l[s], what="gathered decode, source %d" % s)
+    for unique in (False, True):
+        # unique: every holder's split partials stay in the workspace and one launch merges
+        # over splits and holders together
+        ring = B.Ring([q_all[x] for x in sl], [dev(x) for x in rk], [dev(x) for x in rv],
+                      [qpos_all[x] for x in sl], [i32(r["kv_pos"]) for r in ranks],
+                      out_dtype=torch.float32, keep_partials=True, gathered_q=True,
+                      cu_seqlens_kv=[i32(r["cu_kv"]) for r in ranks],
+                      bid=[bid_all[x] for x in sl], unique_bid=unique)
+        out, lse = B.cp_ring_passq_decode(ring)
+        torch.cuda.synchronize()
+        for s in range(n):
+            check(out[s], lse[s], ref_o[s], ref_l[s],
+                  what="gathered decode, source %d, unique_bid %s" % (s, unique))
 
 
 # ---------------------------------------------------------------------------

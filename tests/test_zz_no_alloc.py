@@ -32,13 +32,14 @@ def test_decode_static_equals_decode_on_two_calls_in_a_row(oracle):
     small = _case([300, 31, 1000], [2, 0], 511)
     for what, c in (("first call", big), ("second, smaller call", small)):
         nq = c["q"].shape[0]
-        for odt in (torch.float32, torch.bfloat16):
+        # (both decode paths: split per query, and flat key ranges under CP_SHAPE_UNIQUE_BID)
+        for odt, unique in ((torch.float32, False), (torch.bfloat16, False), (torch.float32, True)):
             ref_o, ref_l = B.cp_attn_decode(c["q"], c["k"], c["v"], c["qp"], c["kp"], c["cu"],
-                                            c["bid"], out_dtype=odt)
+                                            c["bid"], out_dtype=odt, unique_bid=unique)
             out = torch.full((nq, 16, 128), float("nan"), dtype=odt, device="cuda")
             lse = torch.full((nq, 16), float("nan"), dtype=torch.float32, device="cuda")
             B.cp_attn_decode_static(c["q"], c["k"], c["v"], c["qp"], c["kp"], c["cu"], c["bid"],
-                                    out, lse)
+                                    out, lse, unique_bid=unique)
             torch.cuda.synchronize()
             assert torch.equal(out, ref_o), what
             assert torch.equal(lse, ref_l), what
