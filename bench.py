@@ -12,9 +12,11 @@ resident in HBM before the timed region.
 
 Prints ONE JSON line. `value` is causal-effective TFLOP/s (4 * d * N_H * visible pairs).
 `roofline` describes the dominant kernel (the bf16 MFMA attention kernel walking a rank's
-ring), timed with HIP events around whole driver calls in a second pass.
-`cpu_baseline` times the fp64 oracle on a bounded sample of the same workload.
-`aux` carries the bandwidth-bound parts (merge, split-KV decode) in GB/s.
+ring), timed with HIP events around whole driver calls in a second pass (median of the
+timed steps; mean, minimum and maximum beside it). `cpu_baseline` times the fp64 oracle on a
+bounded sample of the same workload. `aux` carries the other configurations, each with a
+`roofline` block of its own: the literal launch-per-step ring, the merge kernel, the 1M-token
+prefill (a subset of ranks), pass-Q decode and the pass-Q partial prefills.
 """
 from __future__ import annotations
 
@@ -46,6 +48,46 @@ def visible_pairs(q_pos: np.ndarray, kv_pos: np.ndarray) -> int:
     """Exact count of (query, key) pairs with kv_pos <= q_pos."""
     ks = np.sort(kv_pos.astype(np.int64))
     return int(np.searchsorted(ks, q_pos.astype(np.int64), side="right").sum())
+
+
+def event_times(fn, reps: int, warmup: int = 1):
+    """HIP-event time of every one of `reps` calls of fn (ms each), on torch's current stream,
+    which is the stream the binding launches on."""
+    for _ in range(warmup):
+        fn()
+    out = []
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out.append(e0.elapsed_time(e1))
+    return out
+
+
+def spread(ms_list, per: float = 1.0):
+    """median / mean / min / max of event times, in microseconds per `per` launches."""
+    a = np.asarray(ms_list, dtype=np.float64) * 1e3 / per
+    return {"us_median": round(float(np.median(a)), 2), "us_mean": round(float(a.mean()), 2),
+            "us_min": round(float(a.min()), 2), "us_max": round(float(a.max()), 2),
+            "samples": int(a.size)}
+
+
+def roofline_block(bound: str, kernel: str, work: float, us: float, traffic=None, **extra):
+    """`work` = algorithmic FLOPs (mfma) or bytes (hbm) of one launch, `us` = its duration."""
+    if bound == "mfma":
+        achieved, peak, unit, key = work / us / 1e6, PEAK_BF16_TFLOPS, "TFLOP/s", "flop_per_launch"
+    else:
+        achieved, peak, unit, key = work / us / 1e3, PEAK_HBM_GBS, "GB/s", "bytes_per_launch"
+    blk = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 2), "peak": peak,
+           "unit": unit, "frac": round(achieved / peak, 4), "traffic": traffic,
+           "us_per_launch": round(us, 2), key: work}
+    if traffic is not None:
+        blk["traffic_source"] = "profiles/ (rocprofv3 --pmc summary stored in the repository; " \
+                                "counters are not read in this run)"
+    blk.update(extra)
+    return blk
 
 
 # ---------------------------------------------------------------------------
@@ -95,7 +137,7 @@ def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
     n = w.n_ranks
     ring = st["parts"]
     total_ms, total_flop, n_launch = 0.0, 0.0, 0
-    merge_ms, merge_bytes = 0.0, 0.0
+    merge_list, merge_bytes, merge_all = [], 0.0, 0.0
     ws = ring.workspace
     for kq in ranks:
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -117,12 +159,18 @@ def kernel_pass_prefill(w: W.Workload, st: dict, ranks):
             total_flop += 4.0 * w.head_dim * w.n_q_heads * visible_pairs(st["pos"][kq],
                                                                          st["pos"][s])
         n_launch += n
-        merge_ms += m0.elapsed_time(m1)
+        merge_list.append(m0.elapsed_time(m1))
+        # Bytes the merge has to move: every LSE, the O row of every NON-EMPTY partial (a
+        # partial whose LSE is -inf has weight zero and its O is never read: a quarter of the
+        # (row, step) pairs of the load-balanced ring), and the merged output.
         rows = ring.out[kq].shape[0] * w.n_q_heads
-        merge_bytes += n * rows * (w.head_dim * 4 + 4) + rows * (w.head_dim * 2 + 4)
+        finite = int(torch.isfinite(ring.partial_lse[:n, :ring.out[kq].shape[0]]).sum().item())
+        merge_bytes += finite * w.head_dim * 4 + n * rows * 4 + rows * (w.head_dim * 2 + 4)
+        merge_all += n * rows * (w.head_dim * 4 + 4) + rows * (w.head_dim * 2 + 4)
     return dict(ms_per_launch=total_ms / n_launch, flop_per_launch=total_flop / n_launch,
-                n_launch=n_launch, merge_ms=merge_ms / len(ranks),
-                merge_bytes=merge_bytes / len(ranks))
+                n_launch=n_launch, merge_ms=float(np.median(merge_list)),
+                merge_ms_all=merge_list, merge_bytes=merge_bytes / len(ranks),
+                merge_bytes_if_all_read=merge_all / len(ranks))
 
 
 def per_call_prefill(w: W.Workload, st: dict, reps: int = 8):
@@ -198,62 +246,97 @@ def build_decode(w: W.Workload):
     return dict(ranks=ranks, q=q, q_pos=q_pos, bid=bid, lengths=lengths)
 
 
-def bench_decode(w: W.Workload, reps: int = 20, graph: bool = False, ring: bool = True):
+def bench_decode(w: W.Workload, reps: int = 20, graph: bool = True, probe_only: bool = False):
+    """Pass-Q decode (Algorithm 4) for 32 sequences x 1 token over 16 virtual ranks, queries
+    gathered: every KV holder answers all 32 queries with one launch over its packed KV (the
+    ranks' KV are distinct buffers, 1.4 GB in all, so nothing is reused from the 256 MB
+    memory-side cache), and one launch merges over splits and holders (Equation 4). Bytes are
+    the algorithmic minimum: every K and V element once, Q, O and LSE; the split partials the
+    kernels exchange are overhead and not counted."""
     st = build_decode(w)
     n = w.n_ranks
-    shape = B.make_shape(B.CP_BF16, w.head_dim, w.n_q_heads, w.n_kv_heads, w.batch,
-                         max(r["total"] for r in st["ranks"]), w.batch)
-    ws = torch.empty(B.cp_workspace_bytes(shape, B.CP_WS_DECODE) + 256, dtype=torch.uint8,
-                     device="cuda")
-    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
-    lse = torch.empty((w.batch, w.n_q_heads), dtype=torch.float32, device="cuda")
-
-    def one_pass():
-        # every virtual rank's whole ring loop in one launch: all 32 queries against its KV
-        for r in st["ranks"]:
-            B.cp_attn_decode(st["q"], r["k"], r["v"], st["q_pos"], r["kv_pos"], r["cu"],
-                             st["bid"], out=out, lse=lse, workspace=ws)
-    sec = time_steps(one_pass, reps, 3)
     kv_bytes = sum(2 * r["total"] * w.n_kv_heads * w.head_dim * 2 for r in st["ranks"])
-    io_bytes = n * (st["q"].numel() * 2 + out.numel() * 4 + lse.numel() * 4)
-    res = dict(workload=w.name, ms_per_rank=sec * 1e3 / n, gbs=(kv_bytes + io_bytes) / sec / 1e9,
-               frac_hbm=(kv_bytes + io_bytes) / sec / 1e9 / PEAK_HBM_GBS,
-               kv_mb_per_rank=kv_bytes / n / 1e6)
-    # All of Algorithm 4 through the driver, queries gathered: 16 decode calls (one per KV
-    # holder, all 32 queries) and the merge across holders of every query's 16 partials
-    if not ring:
-        return res
+    q_bytes = st["q"].numel() * 2
+    out_bytes = w.batch * w.n_q_heads * (w.head_dim * 4 + 4)
+    ring_bytes = kv_bytes + n * q_bytes + out_bytes      # every holder reads the gathered Q
     order = np.argsort(np.arange(w.batch) % n, kind="stable")   # rank r owns b with b % n == r
     per = w.batch // n
     q_g, qpos_g, bid_g = st["q"][order].contiguous(), st["q_pos"][order].contiguous(), _i32(order)
     sl = [slice(r * per, (r + 1) * per) for r in range(n)]
-    gring = B.Ring([q_g[x] for x in sl], [r["k"] for r in st["ranks"]],
-                   [r["v"] for r in st["ranks"]], [qpos_g[x] for x in sl],
-                   [r["kv_pos"] for r in st["ranks"]], out_dtype=torch.float32,
-                   keep_partials=True, gathered_q=True,
-                   cu_seqlens_kv=[r["cu"] for r in st["ranks"]], bid=[bid_g[x] for x in sl])
-    rsec = time_steps(lambda: B.cp_ring_passq_decode(gring), reps, 3)
-    res["ring_ms_per_rank"] = rsec * 1e3 / n
-    res["ring_gbs"] = (kv_bytes + io_bytes) / rsec / 1e9
-    del gring
+
+    def make_ring(unique):
+        return B.Ring([q_g[x] for x in sl], [r["k"] for r in st["ranks"]],
+                      [r["v"] for r in st["ranks"]], [qpos_g[x] for x in sl],
+                      [r["kv_pos"] for r in st["ranks"]], out_dtype=torch.float32,
+                      keep_partials=True, gathered_q=True,
+                      cu_seqlens_kv=[r["cu"] for r in st["ranks"]], bid=[bid_g[x] for x in sl],
+                      unique_bid=unique)
+    gring = make_ring(True)
+    if probe_only:
+        B.cp_ring_passq_decode(gring)
+        torch.cuda.synchronize()
+        return None
+    ts = event_times(lambda: B.cp_ring_passq_decode(gring), reps, 3)
+    us_rank = float(np.median(ts)) * 1e3 / n
+    res = dict(workload=w.name, kv_mb_per_rank=round(kv_bytes / n / 1e6, 4),
+               launches="per KV holder one decode_flat_kernel over all 32 queries (sequence ids "
+                        "unique: CP_SHAPE_UNIQUE_BID); one decode_flat_merge_kernel over splits "
+                        "x holders for the whole ring",
+               ms_per_rank=round(us_rank / 1e3, 5), gbs=round(ring_bytes / n / us_rank / 1e3, 1),
+               frac_hbm=round(ring_bytes / n / us_rank / 1e3 / PEAK_HBM_GBS, 4),
+               per_rank=spread(ts, n))
+    res["roofline"] = roofline_block(
+        "hbm", "decode_flat_kernel (+ 1/16 of the ring's decode_flat_merge_kernel)",
+        ring_bytes / n, us_rank, stored_traffic("decode_flat_kernel", w.name))
+    ref = gring.out_all.clone()
     if graph:
-        # the same 16-rank sequence replayed from one HIP graph (the paper runs decode under
-        # graphs, Section 4.3); the library records kernels only, no memset nodes
-        ref = out.clone()
+        # the same ring replayed from one HIP graph (the paper runs decode under graphs,
+        # Section 4.3); the library records kernels only, no memset nodes
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         g = torch.cuda.CUDAGraph()
         with torch.cuda.stream(side):
-            one_pass()
+            B.cp_ring_passq_decode(gring)
             side.synchronize()
             g.capture_begin(capture_error_mode="relaxed")
-            one_pass()
+            B.cp_ring_passq_decode(gring)
             g.capture_end()
         torch.cuda.synchronize()
-        gsec = time_steps(g.replay, reps, 3)
-        res["graph_ms_per_rank"] = gsec * 1e3 / n
-        res["graph_gbs"] = (kv_bytes + io_bytes) / gsec / 1e9
-        res["graph_matches_eager"] = bool(torch.equal(ref, out))
+        tg = event_times(g.replay, reps, 3)
+        us_g = float(np.median(tg)) * 1e3 / n
+        res["graph"] = {"ms_per_rank": round(us_g / 1e3, 5),
+                        "gbs": round(ring_bytes / n / us_g / 1e3, 1),
+                        "frac_hbm": round(ring_bytes / n / us_g / 1e3 / PEAK_HBM_GBS, 4),
+                        "matches_eager": bool(torch.equal(ref, gring.out_all))}
+        del g
+    # context: the same ring without the promise of unique sequence ids (the split-per-query
+    # kernel, a merge launch per holder and a merge across holders), and single calls
+    oring = make_ring(False)
+    to = event_times(lambda: B.cp_ring_passq_decode(oring), reps, 3)
+    res["ring_without_unique_bid"] = {
+        "ms_per_rank": round(float(np.median(to)) / n, 5),
+        "frac_hbm": round(ring_bytes / n / (float(np.median(to)) * 1e3 / n) / 1e3 / PEAK_HBM_GBS, 4),
+        "max_abs_diff": round(float((oring.out_all - ref).abs().max()), 6)}
+    del oring
+    out = torch.empty((w.batch, w.n_q_heads, w.head_dim), dtype=torch.float32, device="cuda")
+    lse = torch.empty((w.batch, w.n_q_heads), dtype=torch.float32, device="cuda")
+    call_bytes = kv_bytes / n + q_bytes + out_bytes
+    for label, uniq in (("single_call_unique_bid", True), ("single_call", False)):
+        shape = B.make_shape(B.CP_BF16, w.head_dim, w.n_q_heads, w.n_kv_heads, w.batch,
+                             max(r["total"] for r in st["ranks"]), w.batch,
+                             flags=B.CP_SHAPE_UNIQUE_BID if uniq else 0)
+        ws = torch.empty(B.cp_workspace_bytes(shape, B.CP_WS_DECODE) + 256, dtype=torch.uint8,
+                         device="cuda")
+
+        def one_pass():
+            for r in st["ranks"]:
+                B.cp_attn_decode(st["q"], r["k"], r["v"], st["q_pos"], r["kv_pos"], r["cu"],
+                                 st["bid"], out=out, lse=lse, workspace=ws, unique_bid=uniq)
+        tc = event_times(one_pass, max(5, reps // 2), 2)
+        us_c = float(np.median(tc)) * 1e3 / n
+        res[label] = {"us_per_call": round(us_c, 2),
+                      "frac_hbm": round(call_bytes / us_c / 1e3 / PEAK_HBM_GBS, 4),
+                      "launches": "decode kernel + its own merge over the splits"}
     return res
 
 
@@ -345,6 +428,21 @@ def bench_partial_prefill(names, reps: int = 5):
         row["passq_gathered_ms_per_ring"] = round(sec * 1e3, 3)
         row["passq_gathered_us_per_rank"] = round(sec * 1e6 / n, 2)
         row["passq_gathered_tflops"] = round(flop / sec / 1e12, 1)
+        # Roofline of the gathered call of one KV holder (+ 1/16 of the one merge launch).
+        # The arithmetic intensity is (T/N) * 16 FLOP per KV byte: memory-bound at T = 128
+        # (every holder reads its 4.2 MB of K and V once), matrix-bound from T = 1024 on.
+        kv_bytes_rank = sum(int(t.numel()) * 2 * 2 for t in ring.tensors[1]) / n
+        io_bytes_rank = t_new * w.n_q_heads * w.head_dim * 2 + \
+            (t_new // n) * w.n_q_heads * (w.head_dim * 2 + 4)
+        kern = "prefill_mfma_kernel (KV axis split over grid.z) + merge_split_kernel"
+        if t_new * 16 / n < 315:
+            row["roofline"] = roofline_block("hbm", kern, kv_bytes_rank + io_bytes_rank,
+                                             sec * 1e6 / n)
+        else:
+            row["roofline"] = roofline_block("mfma", kern, flop / n, sec * 1e6 / n)
+        row["roofline_literal_step"] = roofline_block(
+            "mfma", kern + ", one launch per ring step (Algorithm 3 as printed)",
+            flop / (n * n), row["passq_us_per_call"])
         row["passq_gathered_max_abs_diff"] = round(max(
             float((a.float() - b.float()).abs().max()) for a, b in zip(gring.out, ring.out)), 5)
         del gring
@@ -470,7 +568,7 @@ def pmc_probe(st):
     torch.cuda.synchronize()
     B.cp_ring_passkv(st["parts"])
     torch.cuda.synchronize()
-    bench_decode(W.WORKLOADS["decode_b32"], reps=1, ring=False)
+    bench_decode(W.WORKLOADS["decode_b32"], probe_only=True)
     print("pmc probe done")
 
 
@@ -485,14 +583,63 @@ def stored_traffic(kernel: str, workload: str):
     return None
 
 
+def bench_prefill_1m_subset(ranks=(0, 9), reps: int = 3):
+    """The 1M-token pass-KV prefill (the largest configuration) on a subset of the 16 virtual
+    ranks: every rank sees the same number of visible pairs by construction, so two ranks'
+    ring walks (64K query tokens each against all sixteen 64K-token KV shards) stand for the
+    ring. Only the chosen ranks' queries are generated; all KV shards are."""
+    w = W.WORKLOADS["prefill_1m"]
+    n = w.n_ranks
+    _, k, v = W.qkv(w, device="cuda", n_q=1)
+    pos = [B.cp_shard_positions(w.t_new, n, r) for r in range(n)]
+    idx = [torch.as_tensor(p.astype(np.int64)).to("cuda") for p in pos]
+    ks = [k[i].contiguous() for i in idx]
+    vs = [v[i].contiguous() for i in idx]
+    del k, v
+    ps = [_i32(p) for p in pos]
+    empty_q = torch.empty((0, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
+    empty_p = torch.empty((0,), dtype=torch.int32, device="cuda")
+    qs = [W.normal(w.seed * 3 + 100 + r, (len(pos[r]), w.n_q_heads, w.head_dim), w.dtype, "cuda")
+          if r in ranks else empty_q for r in range(n)]
+    qps = [ps[r] if r in ranks else empty_p for r in range(n)]
+    flags = [torch.ones(n, dtype=torch.int32, device="cuda") for _ in range(n)]
+    ring = B.Ring(qs, ks, vs, qps, ps, out_dtype=torch.bfloat16, fused_merge=2, arrived=flags)
+    ts = event_times(lambda: B.cp_ring_passkv(ring), reps, 1)
+    pairs = sum(visible_pairs(pos[r], np.arange(w.t_new)) for r in ranks)
+    flop_rank = 4.0 * w.head_dim * w.n_q_heads * pairs / len(ranks)
+    us = float(np.median(ts)) * 1e3 / len(ranks)
+    res = {"workload": w.name, "ranks_timed": list(ranks), "of_ranks": n,
+           "tokens": w.t_new, "ms_per_rank": round(us / 1e3, 3),
+           "tflops": round(flop_rank / us / 1e6, 2), "per_rank": spread(ts, len(ranks)),
+           "roofline": roofline_block("mfma", "prefill_ring_walk_kernel", flop_rank, us)}
+    del ring, qs, ks, vs
+    torch.cuda.empty_cache()
+    return res
+
+
+def bench_padded_shards(w: W.Workload, st: dict, reps: int):
+    """The headline ring with one padded query token (CP_POS_PAD_Q) in every rank's shard,
+    as Algorithm 2 pads shards to equal length: time against the unpadded ring."""
+    n = w.n_ranks
+    qps = []
+    for r in range(n):
+        pp = st["ps"][r].clone()
+        pp[5::1024] = B.CP_POS_PAD_Q      # 8 padded tokens per shard, in 8 different wavefronts
+        qps.append(pp)
+    ring = B.Ring(st["qs"], st["ks"], st["vs"], qps, st["ps"], out_dtype=torch.bfloat16,
+                  fused_merge=2)
+    ts = event_times(lambda: B.cp_ring_passkv(ring), reps, 2)
+    return float(np.median(ts))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="prefill_128k",
                     choices=["prefill_128k", "prefill_1m"])
-    ap.add_argument("--no-aux", action="store_true", help="skip the decode measurement")
+    ap.add_argument("--no-aux", action="store_true", help="skip the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--zero-inputs", action="store_true",
                     help="also time the headline's launches on all-zero Q, K, V (the kernel's "
@@ -526,18 +673,10 @@ def main():
     tflops = flop_step / sec / 1e12
 
     # dominant kernel: the ring walk, one launch per rank; HIP events around a whole driver call
-    # (16 launches and the 16 tile-bound pre-passes, 3.5 us each), repeated `steps` times
-    walk_ms = []
-    for _ in range(args.steps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        B.cp_ring_passkv(ring)
-        e1.record()
-        torch.cuda.synchronize()
-        walk_ms.append(e0.elapsed_time(e1))
-    ms_per_launch = float(np.mean(walk_ms)) / w.n_ranks
+    # (16 launches and the 16 tile-bound pre-passes, 3.5 us each), once per timed step
+    walk_ms = event_times(lambda: B.cp_ring_passkv(ring), args.steps, 0)
+    us_per_launch = float(np.median(walk_ms)) * 1e3 / w.n_ranks
     flop_per_launch = flop_step / w.n_ranks     # every rank sees the same number of pairs
-    achieved = flop_per_launch / (ms_per_launch * 1e-3) / 1e12
     kp = kernel_pass_prefill(w, st, ranks=list(range(w.n_ranks)))
     result = {
         "metric": "per-rank partial-attn+merge TFLOP/s (% bf16 MFMA peak); decode HBM GB/s",
@@ -553,55 +692,72 @@ def main():
                    "flops": "causal-effective 4*d*N_H*pairs",
                    "ms_per_rank": round(sec * 1e3 / w.n_ranks, 3)},
         "frac_of_peak": round(tflops / PEAK_BF16_TFLOPS, 4),
-        "roofline": {"bound": "mfma", "kernel": "prefill_ring_walk_kernel",
-                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": stored_traffic("prefill_ring_walk_kernel", w.name),
-                     "us_per_launch": round(ms_per_launch * 1e3, 2),
-                     "flop_per_launch": flop_per_launch, "launches": w.n_ranks * args.steps},
-        "aux": {"merge": {"ms": round(kp["merge_ms"], 4),
-                          "gbs": round(kp["merge_bytes"] / (kp["merge_ms"] * 1e-3) / 1e9, 1),
-                          "frac_hbm": round(kp["merge_bytes"] / (kp["merge_ms"] * 1e-3) / 1e9 /
-                                            PEAK_HBM_GBS, 4)},
-                # one cp_attn_partial launch per ring step (the kernel prefill_mfma_kernel)
-                "per_step_launch": {
-                    "us_per_launch": round(kp["ms_per_launch"] * 1e3, 2),
-                    "tflops": round(kp["flop_per_launch"] / (kp["ms_per_launch"] * 1e-3) / 1e12, 2),
-                    "flop_per_launch": kp["flop_per_launch"], "launches": kp["n_launch"],
-                    "traffic": stored_traffic("prefill_mfma_kernel", w.name)}},
+        "roofline": roofline_block(
+            "mfma", "prefill_ring_walk_kernel", flop_per_launch, us_per_launch,
+            stored_traffic("prefill_ring_walk_kernel", w.name),
+            launches=w.n_ranks * args.steps, per_launch=spread(walk_ms, w.n_ranks),
+            timing="median over the timed steps of a HIP-event pair around one driver call "
+                   "(16 launches), divided by 16"),
+        "aux": {},
     }
-    result["aux"]["per_call"] = per_call_prefill(w, st)
+    aux = result["aux"]
+    # The literal Algorithm 2: one cp_attn_partial launch per ring step into a stored fp32
+    # partial, then the merge kernel over the rank's 16 partials.
+    us_step = kp["ms_per_launch"] * 1e3
+    aux["per_step_launch"] = {
+        "what": "Algorithm 2 as printed: a launch per ring step (prefill_mfma_kernel), stored "
+                "partials, merge kernel",
+        "roofline": roofline_block("mfma", "prefill_mfma_kernel", kp["flop_per_launch"], us_step,
+                                   stored_traffic("prefill_mfma_kernel", w.name),
+                                   launches=kp["n_launch"])}
+    aux["merge"] = {
+        "what": "merge_kernel over the 16 fp32 partials of one rank (Equation 4); bytes = every "
+                "LSE, the O rows of the non-empty partials, the merged output",
+        "ms": round(kp["merge_ms"], 4), "per_launch": spread(kp["merge_ms_all"]),
+        "bytes_if_every_partial_were_read": kp["merge_bytes_if_all_read"],
+        "roofline": roofline_block("hbm", "merge_kernel", kp["merge_bytes"], kp["merge_ms"] * 1e3,
+                                   stored_traffic("merge_kernel_ring", w.name))}
+    aux["per_call"] = per_call_prefill(w, st)
     if not args.no_aux and w.name == "prefill_128k":
         # a launch per ring step with stored partials and the merge kernel: fp32 partials, and
         # bf16 partials (the width the paper's All2All model assumes)
         parts = st["parts"]
         secp = time_steps(lambda: B.cp_ring_passkv(parts), args.steps, args.warmup)
-        result["aux"]["ring_separate_merge_fp32_partials"] = {
+        aux["ring_separate_merge_fp32_partials"] = {
             "tflops": round(flop_step / secp / 1e12, 2),
+            "frac_of_peak": round(flop_step / secp / 1e12 / PEAK_BF16_TFLOPS, 4),
             "ms_per_rank": round(secp * 1e3 / w.n_ranks, 3)}
         ring16 = B.Ring(st["qs"], st["ks"], st["vs"], st["ps"], st["ps"], out_dtype=torch.bfloat16,
                         part_dtype=torch.bfloat16)
         sec16 = time_steps(lambda: B.cp_ring_passkv(ring16), args.steps, args.warmup)
-        result["aux"]["ring_separate_merge_bf16_partials"] = {
+        aux["ring_separate_merge_bf16_partials"] = {
             "tflops": round(flop_step / sec16 / 1e12, 2),
+            "frac_of_peak": round(flop_step / sec16 / 1e12 / PEAK_BF16_TFLOPS, 4),
             "ms_per_rank": round(sec16 * 1e3 / w.n_ranks, 3)}
         del ring16
         # one launch per ring step, Equation 4 in the attention epilogues
         stp = st["steps"]
         secs = time_steps(lambda: B.cp_ring_passkv(stp), args.steps, args.warmup)
-        result["aux"]["ring_launch_per_step_merge_in_epilogues"] = {
+        aux["ring_launch_per_step_merge_in_epilogues"] = {
             "tflops": round(flop_step / secs / 1e12, 2),
+            "frac_of_peak": round(flop_step / secs / 1e12 / PEAK_BF16_TFLOPS, 4),
             "ms_per_rank": round(secs * 1e3 / w.n_ranks, 3),
             "max_abs_diff_vs_headline": round(max(
                 float((a.float() - b.float()).abs().max()) for a, b in zip(stp.out, ring.out)), 5)}
         # the headline's walk without arrival flags
         walk = B.Ring(st["qs"], st["ks"], st["vs"], st["ps"], st["ps"], out_dtype=torch.bfloat16,
                       fused_merge=2)
-        secw = time_steps(lambda: B.cp_ring_passkv(walk), args.steps, args.warmup)
-        result["aux"]["ring_walk_without_arrival_flags"] = {
+        tw = event_times(lambda: B.cp_ring_passkv(walk), args.steps, 2)
+        secw = float(np.median(tw)) * 1e-3
+        aux["ring_walk_without_arrival_flags"] = {
             "tflops": round(flop_step / secw / 1e12, 2),
             "ms_per_rank": round(secw * 1e3 / w.n_ranks, 3)}
         del walk
+        # the same ring with padded query tokens in every shard (Algorithm 2 pads shards)
+        pad_ms = bench_padded_shards(w, st, args.steps)
+        aux["ring_walk_with_padded_queries"] = {
+            "ms_per_rank": round(pad_ms / w.n_ranks, 3),
+            "vs_unpadded_walk": round(pad_ms * 1e-3 / secw, 4)}
         if args.zero_inputs:
             # the headline's launches on all-zero Q, K, V (same positions, same tile walk, same
             # instruction stream): the part then holds its full clock, so this is the kernel's
@@ -612,7 +768,7 @@ def main():
                            [torch.zeros_like(x) for x in st["vs"]], st["ps"], st["ps"],
                            out_dtype=torch.bfloat16, fused_merge=2)
             secz = time_steps(lambda: B.cp_ring_passkv(zeros), args.steps, args.warmup)
-            result["aux"]["ring_walk_on_zero_inputs"] = {
+            aux["ring_walk_on_zero_inputs"] = {
                 "tflops": round(flop_step / secz / 1e12, 2),
                 "frac_of_peak": round(flop_step / secz / 1e12 / PEAK_BF16_TFLOPS, 4)}
             del zeros
@@ -632,7 +788,7 @@ def main():
                 B.cp_attn_partial(st["qs"][r], st["k_full"], st["v_full"], st["ps"][r],
                                   kv_pos_all, out=outs[r], lse=lses[r], workspace=ws_all)
         seca = time_steps(all_kv, args.steps, args.warmup)
-        result["aux"]["one_launch_per_rank_over_all_kv"] = {
+        aux["one_launch_per_rank_over_all_kv"] = {
             "tflops": round(flop_step / seca / 1e12, 2),
             "ms_per_rank": round(seca * 1e3 / w.n_ranks, 3),
             "max_abs_diff_vs_headline": round(max(
@@ -643,20 +799,20 @@ def main():
     del st, ring
     torch.cuda.empty_cache()
     if not args.no_aux:
-        d = bench_decode(W.WORKLOADS["decode_b32"], graph=True)
-        result["aux"]["decode"] = {k: (round(v, 4) if isinstance(v, float) else v)
-                                   for k, v in d.items()}
+        if w.name == "prefill_128k":
+            aux["prefill_1m"] = bench_prefill_1m_subset()
+        aux["decode"] = bench_decode(W.WORKLOADS["decode_b32"], reps=max(20, args.steps))
         torch.cuda.empty_cache()
-        result["aux"]["hbm_read_probe"] = hbm_read_probe(
-            int(d["kv_mb_per_rank"] * 1e6) // 4096 * 4096)
+        aux["hbm_read_probe"] = hbm_read_probe(
+            int(aux["decode"]["kv_mb_per_rank"] * 1e6) // 4096 * 4096)
         torch.cuda.empty_cache()
-        result["aux"]["partial_prefill"] = bench_partial_prefill(
+        aux["partial_prefill"] = bench_partial_prefill(
             ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
              "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"])
-        result["aux"]["paper_step_shapes"] = bench_paper_step_shapes()
-        result["aux"]["kv_append"] = bench_kv_append()
-        result["aux"]["selector"] = selector_table(tflops * 1e12)
-        result["aux"]["mfma_rate_probe"] = mfma_rate_probe()
+        aux["paper_step_shapes"] = bench_paper_step_shapes()
+        aux["kv_append"] = bench_kv_append()
+        aux["selector"] = selector_table(tflops * 1e12)
+        aux["mfma_rate_probe"] = mfma_rate_probe()
     print(json.dumps(result))
 
 

@@ -326,10 +326,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void decode_kernel(Params p) {
 // regardless of where the sequences begin: a workgroup's first K/V requests then depend on
 // nothing but its index, so they leave at once, and the lookups that tell it whose keys it is
 // reading (cu_seqlens_kv, bid, the query, its position) complete in the shadow of that first
-// round trip. The FW wavefronts of a workgroup share out the range's 16-key units: the first
-// two each by position, every further one from a counter in LDS when a buffer falls free (the
-// memory system does not serve the wavefronts evenly; a fixed deal leaves the workgroup
-// waiting for its unluckiest wavefront). A
+// round trip. The FW wavefronts of a workgroup take the range's 16-key units round-robin (a
+// fixed deal: dealing them out from a counter as buffers fall free was no faster and made the
+// summation order, and so the last bits of the result, vary from run to run). A
 // unit goes HBM -> LDS directly (global_load_lds, no register staging), row-major with the
 // 16-byte chunks of a row permuted on the global side so that the fragment reads are free of
 // bank conflicts (K fragments: ds_read_b128, V^T fragments: ds_read_b64_tr_b16). Every
@@ -352,10 +351,9 @@ constexpr int F_HALF_BYTES = UNIT * D * 2;      // K or V of one unit: 4 KiB
 constexpr int F_POS_OFF = 2 * F_HALF_BYTES;     // kv_pos of the unit's keys, after K and V
 constexpr int F_BUF_BYTES = F_POS_OFF + 256;    // one unit
 constexpr int F_WAVE_LDS = 2 * F_BUF_BYTES;     // two units per wavefront
-constexpr int F_CNT_OFF = FW * F_WAVE_LDS;      // the workgroup's next-unit counter
-constexpr int F_SMEM = F_CNT_OFF + 16;          // 66 KiB: two workgroups per CU
+constexpr int F_SMEM = FW * F_WAVE_LDS;         // 66 KiB: two workgroups per CU
 constexpr int F_UNIT_VMEM_OPS = 9;              // 4 K, 4 V and 1 position request per unit
-static_assert(F_CNT_OFF >= FW * CB_WAVE * 4, "combine buffer aliases the unit buffers");
+static_assert(F_SMEM >= FW * CB_WAVE * 4, "combine buffer aliases the unit buffers");
 
 struct FlatParams {
   const bf16_t* q;
@@ -413,15 +411,6 @@ template <int OFF>
 __device__ __forceinline__ u32x2_t lds_read_tr_at(uint32_t addr) {
   u32x2_t r;
   asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-// Next value of the counter at LDS address `addr` (inline assembly for the same reason).
-__device__ __forceinline__ uint32_t lds_counter_next(uint32_t addr) {
-  uint32_t r, one = 1;
-  asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)"
-               : "=v"(r)
-               : "v"(addr), "v"(one)
-               : "memory");
   return r;
 }
 template <int J>
@@ -533,22 +522,6 @@ __global__ __launch_bounds__(FTHREADS, F_WG_PER_CU) void decode_flat_kernel(Flat
                  : "memory");
   }
 
-  // The counter is set before anything is requested (a full barrier later on would have to
-  // wait for the requests in flight); a bare barrier: no memory operation needs ordering here
-  // but this one LDS write.
-  const uint32_t cnt_addr = (uint32_t)(size_t)(CP_LDS_AS char*)smem + F_CNT_OFF;
-  if (tid == 0) {
-    const uint32_t first = 2 * FW;
-    asm volatile("ds_write_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" ::"v"(cnt_addr), "v"(first)
-                 : "memory");
-  }
-  __builtin_amdgcn_s_barrier();
-  auto next_key = [&]() CP_INL -> int32_t {  // first key of the next unit nobody has taken
-    uint32_t mine = 0;
-    if (lane == 0) mine = lds_counter_next(cnt_addr);
-    const uint32_t u = __builtin_amdgcn_readfirstlane(mine);
-    return u < (uint32_t)(p.wg_keys / UNIT) ? w0 + (int32_t)u * UNIT : w1;
-  };
   int32_t key_a = w0 + wave * UNIT;        // unit in buf0
   int32_t key_b = key_a + FW * UNIT;       // unit in buf1
   issue_unit(buf0, key_a);
@@ -766,14 +739,14 @@ __global__ __launch_bounds__(FTHREADS, F_WG_PER_CU) void decode_flat_kernel(Flat
     else vmem_wait<0>();
     process_unit(IntC<0>{}, key_a);
     lds_reads_done();  // before the buffer is refilled
-    key_a = next_key();
+    key_a = key_b + FW * UNIT;
     if (key_a < w1) issue_unit(buf0, key_a);
     if (key_b >= w1) break;
     if (key_a < w1) vmem_wait<F_UNIT_VMEM_OPS>();
     else vmem_wait<0>();
     process_unit(IntC<1>{}, key_b);
     lds_reads_done();
-    key_b = next_key();
+    key_b = key_a + FW * UNIT;
     if (key_b < w1) issue_unit(buf1, key_b);
   }
   // sequences that end inside the range after this wavefront's last unit
@@ -858,13 +831,11 @@ __host__ __device__ inline FlatParts flat_parts(int32_t a, int32_t b, int32_t wg
 }
 
 // Equation 4 over the flat decode partials of one query row (query, head), over all holders.
-// One workgroup of 16 wavefronts per row. Thread t looks up part t of the row (its slot and
+// One workgroup of MW wavefronts per row. Thread t looks up part t of the row (its slot and
 // LSE); the largest LSE and the weights are reduced across the workgroup; then the wavefronts
 // share out the parts, every lane accumulating two channels of the parts its wavefront takes
-// (four loads in flight per lane), and the 16 sums are added up in LDS.
+// (four loads in flight per lane), and the MW sums are added up in LDS.
 constexpr int kMaxHolders = CP_MAX_PARTS;
-constexpr int MW = 16;               // wavefronts per merge workgroup
-constexpr int MTHREADS = MW * 64;
 struct FlatMergeParams {
   const float* part_out[kMaxHolders];
   const float* part_lse[kMaxHolders];
@@ -877,10 +848,13 @@ struct FlatMergeParams {
   int32_t n_q_heads;
 };
 
-template <typename TO>
-__global__ __launch_bounds__(MTHREADS) void decode_flat_merge_kernel(FlatMergeParams mp,
+// MW wavefronts per workgroup: 16 for a ring of holders, 2 for the few parts of one call.
+template <typename TO, int MW>
+__global__ __launch_bounds__(MW * 64) void decode_flat_merge_kernel(FlatMergeParams mp,
                                                                      TO* __restrict__ out,
                                                                      float* __restrict__ lse_out) {
+  constexpr int MTHREADS = MW * 64;
+  static_assert(MTHREADS >= D, "one thread per channel writes the row");
   __shared__ int part_begin[kMaxHolders + 1];  // first part index of every holder
   __shared__ int holder_lo[kMaxHolders], holder_mains[kMaxHolders];
   __shared__ float red[MW];
@@ -891,16 +865,24 @@ __global__ __launch_bounds__(MTHREADS) void decode_flat_merge_kernel(FlatMergePa
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int qi = row / mp.n_q_heads, h = row - qi * mp.n_q_heads;
   const int s = mp.bid[qi];
+  // thread k looks up holder k's slots of this sequence (one round trip for all holders),
+  // thread 0 then lines the holders' parts up
+  if (tid < mp.n_holders) {
+    const int k = tid;
+    const FlatParts fp =
+        flat_parts(mp.cu_kv[k][s], mp.cu_kv[k][s + 1], mp.wg_keys[k], mp.total_kv[k]);
+    const int mains = max(0, fp.g_hi - fp.g_lo + 1);
+    holder_lo[k] = fp.g_lo;
+    holder_mains[k] = mains;
+    part_begin[k + 1] = mains + (fp.tail ? FW : 0);
+  }
+  __syncthreads();
   if (tid == 0) {
     int n = 0;
     for (int k = 0; k < mp.n_holders; ++k) {
-      const FlatParts fp =
-          flat_parts(mp.cu_kv[k][s], mp.cu_kv[k][s + 1], mp.wg_keys[k], mp.total_kv[k]);
-      const int mains = max(0, fp.g_hi - fp.g_lo + 1);
+      const int c = part_begin[k + 1];
       part_begin[k] = n;
-      holder_lo[k] = fp.g_lo;
-      holder_mains[k] = mains;
-      n += mains + (fp.tail ? FW : 0);
+      n += c;
     }
     part_begin[mp.n_holders] = n;
   }
@@ -1080,12 +1062,22 @@ int launch_decode_flat_merge(int n_holders, const cp_shape* shapes, void* const*
   mp.n_q_heads = shapes[0].n_q_heads;
   const int64_t rows = n_q * shapes[0].n_q_heads;
   if (rows > 0x7fffffffLL) return CP_ERR_SHAPE;
-  if (out_dtype == CP_FP32)
-    hipLaunchKernelGGL(decode_flat_merge_kernel<float>, dim3((unsigned)rows), dim3(MTHREADS), 0,
-                       stream, mp, (float*)out, lse);
-  else
-    hipLaunchKernelGGL(decode_flat_merge_kernel<bf16_t>, dim3((unsigned)rows), dim3(MTHREADS), 0,
-                       stream, mp, (bf16_t*)out, lse);
+  const dim3 grid((unsigned)rows);
+  if (n_holders == 1) {
+    if (out_dtype == CP_FP32)
+      hipLaunchKernelGGL((decode_flat_merge_kernel<float, 2>), grid, dim3(128), 0, stream, mp,
+                         (float*)out, lse);
+    else
+      hipLaunchKernelGGL((decode_flat_merge_kernel<bf16_t, 2>), grid, dim3(128), 0, stream, mp,
+                         (bf16_t*)out, lse);
+  } else {
+    if (out_dtype == CP_FP32)
+      hipLaunchKernelGGL((decode_flat_merge_kernel<float, 16>), grid, dim3(1024), 0, stream, mp,
+                         (float*)out, lse);
+    else
+      hipLaunchKernelGGL((decode_flat_merge_kernel<bf16_t, 16>), grid, dim3(1024), 0, stream, mp,
+                         (bf16_t*)out, lse);
+  }
   return check_launch();
 }
 

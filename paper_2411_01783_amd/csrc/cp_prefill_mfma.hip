@@ -48,6 +48,7 @@ constexpr int MAX_LIVE = 512;   // live-tile list entries per chunk (8 wavefront
 constexpr int OUT_STRIDE = D * 4 + 16;    // epilogue staging: one fp32 output row + pad
 constexpr float kRescaleSlack = 8.f;               // log2 units
 constexpr float kOverflowSum = 1099511627776.f;    // 2^40: a block sum beyond it is redone
+constexpr float kDeadRowRef = 1e30f;               // reference of a row that sees no key
 constexpr int kMinTilesPerSplit = 1;
 
 struct Params {

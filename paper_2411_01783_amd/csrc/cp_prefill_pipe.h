@@ -425,9 +425,10 @@ __device__ __forceinline__ void prefill_body(const Params& p,
   }
 
   // ---- query position range of the wavefront and of the workgroup ----
-  int w_qmin = row_ok ? qp : INT32_MAX, w_qmax = qp;
-  // lower bounds of the rows that can see anything (a padded query has the empty range)
+  // rows that can see anything: a padded query (CP_POS_PAD_Q) and the rows past the end of
+  // the shard cannot, and stay out of the ranges below
   const bool sees = row_ok && qp >= 0;
+  int w_qmin = sees ? qp : INT32_MAX, w_qmax = qp;
   int w_lomin = BAND && sees ? ql : INT32_MAX, w_lomax = BAND && sees ? ql : INT32_MIN;
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -459,7 +460,11 @@ __device__ __forceinline__ void prefill_body(const Params& p,
 
   bool have_ref = false;  // every row of the wavefront has a finite reference maximum
   PipeRegs R;
-  R.m_run = -INFINITY;  // reference max of scaled scores (log2 domain)
+  // Reference max of scaled scores (log2 domain). A row that can see nothing gets a finite
+  // reference no score reaches: its exponentials are all zero whichever softmax form its
+  // wavefront takes (so one padded row does not keep the other 31 on the masked form), its
+  // denominator stays zero, and the epilogue writes O = 0, LSE = -inf for it.
+  R.m_run = sees ? -INFINITY : kDeadRowRef;
   R.l_run = 0.f;        // running denominator over this lane's half of the keys
 #pragma unroll
   for (int db = 0; db < 4; ++db)

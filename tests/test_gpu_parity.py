@@ -109,6 +109,24 @@ def test_mfma_partial_random_positions(oracle, tq, tkv, nh, nkv):
         check(o, l, *ref, what="out dtype %s" % odt)
 
 
+def test_mfma_partial_padded_queries_among_fully_visible_tiles(oracle):
+    """Padded query tokens (CP_POS_PAD_Q) inside wavefronts whose other rows see every key: the
+    wavefront keeps the mask-free softmax form, the padded rows still come out as O = 0,
+    LSE = -inf. Unsplit walk (128 row blocks) and a split one."""
+    for tq, tkv in ((2048, 1100), (160, 1100)):
+        q, q64 = randn(71, (tq, 16, 128))
+        k, k64 = randn(72, (tkv, 1, 128))
+        v, v64 = randn(73, (tkv, 1, 128))
+        kp = np.arange(tkv)
+        qp = np.arange(tq) + tkv               # every key visible to every real query
+        qp[[0, 3, 17, 64, 65, tq // 2, tq - 1]] = B.CP_POS_PAD_Q
+        ref = oracle.attn(q64, k64, v64, qp, kp)
+        assert np.isneginf(ref[1][3]).all() and np.isfinite(ref[1][4]).all()
+        for odt in (torch.float32, torch.bfloat16):
+            o, l = gpu_partial(q, k, v, qp, kp, out_dtype=odt)
+            check(o, l, *ref, what="padded queries, tq %d, out %s" % (tq, odt))
+
+
 def test_mfma_partial_seeded_shape_sweep(oracle):
     """Twelve seeded shapes inside the documented limits: ragged row blocks and tiles, every
     head grouping, split and unsplit walks, sorted and shuffled positions, pads."""
@@ -701,7 +719,8 @@ def test_hbm_read_probe_reads_every_chunk_once(n_words, n_wg):
     host = rng.integers(0, 2 ** 31 - 1, n_words, dtype=np.int32)
     buf = torch.as_tensor(host).to("cuda")
     sink = torch.zeros(n_wg * 256, dtype=torch.int32, device="cuda")
-    assert B.cp_probe_hbm_read(buf, n_wg, sink) == n_words * 4
+    from bench_support import probes
+    assert probes.hbm_read(buf, n_wg, sink) == n_words * 4
     torch.cuda.synchronize()
     # the xor of what the threads folded is the xor of the buffer iff no chunk was skipped or
     # read twice (random words: a chunk read twice cancels, a skipped one is missing)
