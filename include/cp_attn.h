@@ -315,9 +315,18 @@ typedef struct {
    * a buffer of its own that is complete before its flag is set and is not written again
    * while the kernel runs (N receive buffers per rank instead of two). The wait is bounded:
    * one thread per workgroup polls at most spin_limit (>= 1) times, a memory round trip and
-   * a short sleep (a few microseconds in all) apart; if the flag stays zero the workgroup leaves that shard out and sets *ring_error
-   * (device int32, required with arrived; the caller zeroes it) to 1 - the outputs are then
-   * not meaningful, but every kernel ends.
+   * a short sleep (a few microseconds in all) apart; if the flag stays zero the workgroup
+   * leaves that shard out and sets bit j of ring_error[k] (device int32 [n_ranks], required
+   * with arrived; the caller zeroes it): which steps of which ranks gave up can be read off it.
+   * The outputs of such a rank are then not meaningful, but every kernel ends.
+   * Limit of the contract: it relies on no line of a step's buffer being in a cache of this
+   * GPU when its flag is seen. Within one launch that holds because the buffer is read only
+   * after its flag. From one launch to the next (the next layer, the next call) it holds if
+   * the caches are invalidated between the last read of the old contents and the arrival of
+   * the new ones, which the acquire at the start of a kernel launched after the old reader
+   * has finished provides; so a buffer may be reused by a later call, but not twice within
+   * one launch, and not while a launch that read its old contents is still running (two walks
+   * overlapping on two streams). A caller that cannot guarantee this uses a fresh buffer.
    */
   const int32_t* const* arrived;
   int32_t* ring_error;

@@ -460,7 +460,7 @@ class Ring:
         if arrived is not None:
             self._arrived = (_vp * n)(*[_ptr(t) for t in arrived])
             dsc.arrived = ctypes.cast(self._arrived, ctypes.POINTER(_vp))
-            self.ring_error = torch.zeros(1, dtype=torch.int32, device=dev)
+            self.ring_error = torch.zeros(n, dtype=torch.int32, device=dev)   # per rank: bit j = step j
             dsc.ring_error = _ptr(self.ring_error)
             dsc.spin_limit = spin_limit
         if cu_seqlens_q is not None:   # packed prefill batch
@@ -490,7 +490,7 @@ class Ring:
         if self.arrived is None:
             return False
         torch.cuda.synchronize()
-        return int(self.ring_error.item()) != 0
+        return bool((self.ring_error != 0).any().item())
 
     def partial(self, a: int, b: int):
         """Partial (O, LSE) of rank a's queries against rank b's KV (keep_partials only)."""

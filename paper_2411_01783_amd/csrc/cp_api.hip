@@ -535,7 +535,8 @@ int ring_rank_walk(const cp_ring_desc* d, const RingWork& w, const RingSlots& sl
   const int32_t* arrived = d->arrived != nullptr ? d->arrived[a] : nullptr;
   float* const lse_out = d->lse != nullptr ? d->lse[a] : nullptr;
   return launch_prefill_mfma_ring(s, resolve_scale(s.softmax_scale, s.head_dim), d->q[a],
-                                  d->q_pos[a], n, k, v, pos, bounds, n_kv, arrived, d->ring_error,
+                                  d->q_pos[a], n, k, v, pos, bounds, n_kv, arrived,
+                                  d->ring_error != nullptr ? d->ring_error + a : nullptr,
                                   d->spin_limit, d->out[a],
                                   lse_out != nullptr ? lse_out : slots.lse(0),  // LSE not wanted
                                   d->out_dtype, st);

@@ -73,8 +73,8 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
 // rank's merged O / LSE. s.total_kv is the largest shard (it decides, with total_q, whether
 // the launch would split its KV axis, which the walk does not support).
 // `arrived` (device, or NULL): int32 per step, the kernel waits (at most spin_limit polls) for
-// a nonzero value before it reads step j's shard; a wait that gives up sets *error = 1 and
-// leaves the shard out.
+// a nonzero value before it reads step j's shard; a wait that gives up sets bit j of *error
+// and leaves the shard out.
 bool prefill_ring_walk_applies(const cp_shape& s, int n_shards);
 int launch_prefill_mfma_ring(const cp_shape& s, float scale, const void* q, const int32_t* q_pos,
                              int n_shards, const void* const* k, const void* const* v,

@@ -92,7 +92,7 @@ struct RingShard {
 struct RingTable {
   RingShard shard[kMaxRingShards];
   const int32_t* arrived;  // or NULL: [n_shards], nonzero once the shard of step j may be read
-  int32_t* error;          // set to 1 when a wait gave up (only used with `arrived`)
+  int32_t* error;          // bit j is set when the wait of step j gave up (only with `arrived`)
   int32_t n_shards;
   int32_t spin_limit;      // polls per shard before giving up
 };

@@ -315,7 +315,7 @@ __device__ __forceinline__ int ring_shards(const NoRing&) { return 1; }
 // was being walked (so a shard that arrived in time costs no round trip here); if that was
 // zero it polls (uncached loads, a short sleep between them, at most ring.spin_limit of them).
 // The whole workgroup learns the outcome through LDS; false = the flag never came up:
-// *ring.error is set and the caller leaves the shard out. Every wait ends.
+// bit `shard` of *ring.error is set and the caller leaves the shard out. Every wait ends.
 __device__ __forceinline__ int ring_flag(const RingTable& ring, int step) {
   return __hip_atomic_load(ring.arrived + step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
@@ -345,7 +345,7 @@ __device__ __forceinline__ bool ring_enter(const RingTable& ring, int shard, int
         __builtin_amdgcn_s_sleep(32);
       }
     }
-    if (!ok) *ring.error = 1;
+    if (!ok) atomicOr(ring.error, 1 << shard);  // which step gave up (n_shards <= 32)
     *slot = ok;
     // a look at the next step's flag, used when the walk gets there
     peek = shard + 1 < ring.n_shards ? ring_flag(ring, shard + 1) : 0;

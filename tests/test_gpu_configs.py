@@ -15,11 +15,14 @@ from paper_2411_01783_amd import workloads as W
 pytestmark = pytest.mark.gpu
 
 
-def _sample_rows(n_rows, chunk, rng, extra=8):
-    """Row indices of one rank's shard: chunk edges plus a seeded random sample."""
-    edges = [0, 1, chunk - 1, chunk, chunk + 1, n_rows - 1]
+def _sample_rows(n_rows, chunk, rng, extra=8, at_least=0):
+    """Row indices of one rank's shard: the first and last rows of both chunks it owns (the
+    rows either side of the boundary between them included) plus a seeded random sample."""
+    edges = [0, 1, chunk - 2, chunk - 1, chunk, chunk + 1, n_rows - 2, n_rows - 1]
     rows = set(int(e) for e in edges if 0 <= e < n_rows)
     rows.update(int(x) for x in rng.integers(0, n_rows, size=extra))
+    while len(rows) < min(at_least, n_rows):
+        rows.add(int(rng.integers(0, n_rows)))
     return np.array(sorted(rows))
 
 
@@ -51,8 +54,8 @@ def test_prefill_128k_passkv_ring_sampled(oracle, fused_merge):
     rng = np.random.default_rng(w.seed)
     chunk = w.t_new // (2 * w.n_ranks)
     worst = 0.0
-    for r in (0, 6, 15):
-        rows = _sample_rows(len(pos[r]), chunk, rng)
+    for r in range(w.n_ranks):     # every rank, 64 query tokens each (all 16 heads)
+        rows = _sample_rows(len(pos[r]), chunk, rng, at_least=64)
         tok = pos[r][rows]
         ref_o, ref_l = oracle.attn(_gather_f64(q, tok), k64, v64, tok, np.arange(w.t_new))
         sel = torch.as_tensor(rows).to("cuda")
@@ -117,12 +120,12 @@ def test_prefill_1m_ring_walk_sampled(oracle):
     ring = B.Ring(qs, ks, vs, ps, ps, out_dtype=torch.bfloat16, fused_merge=2, arrived=flags)
     out, lse = B.cp_ring_passkv(ring)
     torch.cuda.synchronize()
-    assert int(ring.ring_error.item()) == 0
+    assert not ring.arrival_failed()
     k64, v64 = W.to_f64(k), W.to_f64(v)
     rng = np.random.default_rng(w.seed + 1)
     chunk = w.t_new // (2 * n)
-    for r in (0, 9):
-        rows = _sample_rows(len(pos[r]), chunk, rng, extra=2)
+    for r in (0, 5, 9, 15):
+        rows = _sample_rows(len(pos[r]), chunk, rng, at_least=16)
         tok = pos[r][rows]
         ref_o, ref_l = oracle.attn(_gather_f64(q, tok), k64, v64, tok, np.arange(w.t_new))
         sel = torch.as_tensor(rows).to("cuda")
@@ -132,7 +135,7 @@ def test_prefill_1m_ring_walk_sampled(oracle):
 
 @pytest.mark.parametrize("gathered", [False, True])
 @pytest.mark.parametrize("name", ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
-                                  "partial_prefill_128k_t8192"])
+                                  "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"])
 def test_partial_prefill_passq_ring_sampled(oracle, name, gathered):
     # gathered: the 16 query shards back to back, one call per KV holder for all 16 steps
     w = W.WORKLOADS[name]

@@ -313,7 +313,7 @@ def test_ring_walk_in_one_launch_matches_unsharded(oracle, n, t, flags):
         out, lse = B.cp_ring_passkv(ring)
         torch.cuda.synchronize()
         if flags:
-            assert int(ring.ring_error.item()) == 0
+            assert not ring.arrival_failed()
         assert torch.isneginf(lse[0][5]).all() and (out[0][5] == 0).all()
         got_o = torch.stack([out[where[int(r)][0]][where[int(r)][1]] for r in rows])
         got_l = torch.stack([lse[where[int(r)][0]][where[int(r)][1]] for r in rows])
@@ -349,7 +349,8 @@ def test_ring_walk_gives_up_on_a_shard_that_never_arrives(oracle):
                   fused_merge=2, arrived=arrived, spin_limit=3)
     out, lse = B.cp_ring_passkv(ring)
     torch.cuda.synchronize()
-    assert int(ring.ring_error.item()) == 1 and ring.arrival_failed()
+    # rank 2, step 1 and nothing else
+    assert ring.ring_error.tolist() == [0, 0, 1 << 1, 0] and ring.arrival_failed()
     rows = np.r_[0:16, 1000:1016, 2032:2048]
     for a in (0, 1, 3):
         tok = pos[a][rows]
@@ -968,4 +969,4 @@ def test_ring_walk_under_a_hip_graph(oracle):
         for r in range(n):
             assert torch.equal(ring.out[r], eager[i][0][r]), "replay %d rank %d" % (i, r)
             assert torch.equal(ring.lse[r], eager[i][1][r]), "replay %d rank %d" % (i, r)
-    assert int(ring.ring_error.item()) == 0
+    assert not ring.arrival_failed()

@@ -574,26 +574,6 @@ def test_multi_turn_replay_over_the_persistent_cache(oracle):
 
 
 # ---------------------------------------------------------------------------
-# planted mistakes: each plausible slip in a re-implementation must trip a pin above
-# ---------------------------------------------------------------------------
-
-def test_pins_detect_planted_mistakes(oracle):
-    t, d = 12, 4
-    q, k, v = rnd(181, t, 2, d), rnd(182, t, 1, d), rnd(183, t, 1, d)
-    good_o, good_l = oracle.unsharded_causal(q, k, v)
-    pos = np.arange(t)
-    # exclusive diagonal
-    o, l = oracle.attn(q, k, v, pos - 1, pos)
-    assert np.isneginf(l[0]).all() and not np.allclose(o[1:], good_o[1:])
-    # missing scale
-    _, l = oracle.attn(q, k, v, pos, pos, scale=1.0)
-    assert not np.allclose(l[1:], good_l[1:])
-    # transposed mask (key sees query)
-    o, _ = oracle.attn(q, k, v, -pos, -pos)
-    assert not np.allclose(o, good_o)
-
-
-# ---------------------------------------------------------------------------
 # pass-KV / pass-Q selection (Section 3.3, Appendix C, Appendix D)
 # ---------------------------------------------------------------------------
 
@@ -647,6 +627,9 @@ def test_selector_all2all_lowers_the_pass_q_region(oracle):
     # Appendix C: counting the All2All can only move decisions from pass-Q to pass-KV, and at
     # 2.5 % miss rate on CP4 (T = 3200) pass-Q still wins, as the paper measures
     assert oracle.select_order(3200, 124800, **LLAMA405, **CP4, rule="all2all") == "pass-Q"
+    # the breakdown table's other column: at 10 % miss rate (T = 12800) SendRecv is hidden under
+    # the attention of a ring step, so nothing of pass-KV is exposed and it stays the choice
+    assert oracle.select_order(12800, 115200, **LLAMA405, **CP4, rule="all2all") == "pass-KV"
     moved = 0
     for t in range(200, 6000, 100):
         for total in (16000, 64000, 128000, 512000):
