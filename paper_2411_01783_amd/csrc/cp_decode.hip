@@ -476,6 +476,14 @@ __global__ __launch_bounds__(FTHREADS, F_WG_PER_CU) void decode_flat_kernel(Flat
   // a register, so the only waits are the counted ones below.
   const uint32_t tok_stride = (uint32_t)p.n_kv_heads * D;
   const int l_row = lane >> 4, l_pos = lane & 15;
+  // per-lane element offsets of the eight requests of a full unit
+  uint32_t koff[4], voff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = i * 4 + l_row;
+    koff[i] = (uint32_t)row * tok_stride + ((l_pos ^ row) << 3);
+    voff[i] = (uint32_t)row * tok_stride + ((l_pos ^ ((row & 3) << 2)) << 3);
+  }
   auto issue_unit = [&](char* buf, int32_t key_req) CP_INL {
     // (a wavefront without a unit of its own still sends the requests, for the range's last
     // key: every wavefront then has the same number of operations in flight)
@@ -483,13 +491,21 @@ __global__ __launch_bounds__(FTHREADS, F_WG_PER_CU) void decode_flat_kernel(Flat
     const int last = min(UNIT, w1 - key0) - 1;
     const bf16_t* kt = p.k + (int64_t)key0 * tok_stride + kvh * D;
     const bf16_t* vt = p.v + (int64_t)key0 * tok_stride + kvh * D;
+    if (__builtin_expect(last == UNIT - 1, 1)) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = i * 4 + l_row;
-      const uint32_t roff = (uint32_t)min(row, last) * tok_stride;
-      load_lds16_stream(kt + roff + ((l_pos ^ row) << 3), buf + i * 1024);
-      load_lds16_stream(vt + roff + ((l_pos ^ ((row & 3) << 2)) << 3),
-                        buf + F_HALF_BYTES + i * 1024);
+      for (int i = 0; i < 4; ++i) {
+        load_lds16_stream(kt + koff[i], buf + i * 1024);
+        load_lds16_stream(vt + voff[i], buf + F_HALF_BYTES + i * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int row = i * 4 + l_row;
+        const uint32_t roff = (uint32_t)min(row, last) * tok_stride;
+        load_lds16_stream(kt + roff + ((l_pos ^ row) << 3), buf + i * 1024);
+        load_lds16_stream(vt + roff + ((l_pos ^ ((row & 3) << 2)) << 3),
+                          buf + F_HALF_BYTES + i * 1024);
+      }
     }
     __builtin_amdgcn_global_load_lds((const CP_GLB_AS void*)(p.kv_pos + key0 + min(l_pos, last)),
                                      (CP_LDS_AS void*)(buf + F_POS_OFF), 4, 0, 0);
@@ -652,10 +668,8 @@ __global__ __launch_bounds__(FTHREADS, F_WG_PER_CU) void decode_flat_kernel(Flat
 
   // S^T and O^T of the keys [lo, hi) of the unit at t0 (in unit buffer BUF) for the current
   // sequence
-  // (BOUNDS false: the whole unit belongs to the sequence, only the positions mask)
-  auto unit_compute = [&](auto bufc, auto boundsc, int32_t t0, int32_t lo, int32_t hi) CP_INL {
+  auto unit_compute = [&](auto bufc, int32_t t0, int32_t lo, int32_t hi) CP_INL {
     constexpr int BO = decltype(bufc)::value * F_BUF_BYTES;
-    constexpr bool BOUNDS = decltype(boundsc)::value != 0;
     u32x4_t kp4 = lds_read_b128_at<BO>(paddr);
     u32x4_t kf0 = lds_read_b128_at<BO>(kaddr[0]), kf1 = lds_read_b128_at<BO>(kaddr[1]);
     u32x4_t kf2 = lds_read_b128_at<BO>(kaddr[2]), kf3 = lds_read_b128_at<BO>(kaddr[3]);
@@ -674,8 +688,9 @@ __global__ __launch_bounds__(FTHREADS, F_WG_PER_CU) void decode_flat_kernel(Flat
     float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int32_t kidx = t0 + kg * 4 + i;
-      if ((int32_t)kp4[i] > cur.qp || (BOUNDS && (kidx < lo || kidx >= hi))) s[i] = -INFINITY;
+      // (lo <= key index < hi as one unsigned comparison)
+      const uint32_t off = (uint32_t)(t0 + kg * 4 + i - lo);
+      if ((int32_t)kp4[i] > cur.qp || off >= (uint32_t)(hi - lo)) s[i] = -INFINITY;
       mx = fmaxf(mx, s[i]);
     }
     mx = quad_max(mx);
@@ -716,18 +731,16 @@ __global__ __launch_bounds__(FTHREADS, F_WG_PER_CU) void decode_flat_kernel(Flat
   bool more = true;
   auto process_unit = [&](auto bufc, int32_t key0) CP_INL {
     const int32_t t1 = min(key0 + UNIT, w1);
-    if (__builtin_expect(more && cur.lo <= key0 && key0 + UNIT <= min(cur.hi, w1), 1)) {
-      // the usual case: all 16 keys belong to the current sequence
-      if (cur.qi >= 0) unit_compute(bufc, IntC<0>{}, key0, 0, 0);
-      return;
-    }
-    while (more && cur.hi <= key0) {  // sequences that ended before this unit
-      flush_tail();
-      more = next_seq();
-    }
+    // (one call site for the products: two would make the compiler shuttle the accumulators
+    // between register sets at every unit)
     while (more) {
-      if (cur.qi >= 0) unit_compute(bufc, IntC<1>{}, key0, max(cur.lo, key0), min(cur.hi, t1));
-      if (cur.hi >= t1) break;
+      if (__builtin_expect(cur.hi <= key0, 0)) {  // a sequence that ended before this unit
+        flush_tail();
+        more = next_seq();
+        continue;
+      }
+      if (cur.qi >= 0) unit_compute(bufc, key0, max(cur.lo, key0), min(cur.hi, t1));
+      if (__builtin_expect(cur.hi >= t1, 1)) break;
       flush_tail();  // the sequence ends inside this unit
       more = next_seq();
     }
