@@ -285,9 +285,12 @@ def bench_decode(w: W.Workload, reps: int = 20, graph: bool = True, probe_only: 
                ms_per_rank=round(us_rank / 1e3, 5), gbs=round(ring_bytes / n / us_rank / 1e3, 1),
                frac_hbm=round(ring_bytes / n / us_rank / 1e3 / PEAK_HBM_GBS, 4),
                per_rank=spread(ts, n))
+    t_kernel = stored_traffic("decode_flat_kernel", w.name)
+    t_merge = stored_traffic("decode_flat_merge_kernel", w.name)
     res["roofline"] = roofline_block(
         "hbm", "decode_flat_kernel (+ 1/16 of the ring's decode_flat_merge_kernel)",
-        ring_bytes / n, us_rank, stored_traffic("decode_flat_kernel", w.name))
+        ring_bytes / n, us_rank,
+        None if t_kernel is None or t_merge is None else t_kernel + t_merge / n)
     ref = gring.out_all.clone()
     if graph:
         # the same ring replayed from one HIP graph (the paper runs decode under graphs,

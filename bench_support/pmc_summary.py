@@ -5,12 +5,16 @@ The raw counters are scaled by what the same counters read for the probe's plain
 kernel, which reads and writes a known number of bytes; the factor is printed in the
 summary.
 
-usage: python -m paper_2411_01783_amd.pmc_summary FETCH.csv WRITE.csv OUT_DIR WORKLOAD "CMD"
+usage: python -m bench_support.pmc_summary FETCH.csv WRITE.csv OUT_DIR WORKLOAD "CMD"
 
 A third run of the same probe with matrix-pipe and LDS counters is summarised by
-       python -m paper_2411_01783_amd.pmc_summary --mfma COUNTERS.csv OUT_DIR WORKLOAD "CMD"
+       python -m bench_support.pmc_summary --mfma COUNTERS.csv OUT_DIR WORKLOAD "CMD"
 into <kernel>_<workload>_mfma_counters.txt: mean counter values per launch, the share of
 SIMD cycles with the matrix pipe busy, the clock the launch ran at and the FLOPs it executed.
+
+The per-kernel table (one row per kernel and grid) of a `rocprofv3 --kernel-trace --stats
+--output-format csv` run of bench.py, together with the JSON line bench.py printed in that very run, is written by
+       python -m bench_support.pmc_summary --stats KERNEL_TRACE.csv BENCH_LINE.json OUT.txt "CMD"
 """
 from __future__ import annotations
 
@@ -21,7 +25,9 @@ import sys
 
 # kernel-name substring -> tag of the summary file (first match wins)
 KERNELS = [("prefill_ring_walk_kernel", "prefill_ring_walk_kernel"),
-           ("prefill_mfma_kernel", "prefill_mfma_kernel"), ("decode_kernel", "decode_kernel"),
+           ("prefill_mfma_kernel", "prefill_mfma_kernel"),
+           ("decode_flat_merge_kernel", "decode_flat_merge_kernel"),
+           ("decode_flat_kernel", "decode_flat_kernel"), ("decode_kernel", "decode_kernel"),
            ("merge_split_kernel", "merge_kernel_split"), ("merge_kernel", "merge_kernel_ring")]
 COPY_MARK = "MulFunctor"
 
@@ -97,9 +103,94 @@ def mfma_main():
         print(out)
 
 
+def short_name(name: str) -> str:
+    """A readable kernel name: our namespace spelled plainly, argument lists cut. (The
+    profiler leaves names with a __bf16 template argument mangled; those are spelled out here.)"""
+    import re
+    m = re.match(r"_ZN2cp12_GLOBAL__N_1(\d+)", name)
+    if m:
+        n = int(m.group(1))
+        base = name[m.end():m.end() + n]
+        rest = name[m.end() + n:]
+        args = []
+        if rest.startswith("I"):
+            i = 1
+            while i < len(rest) and rest[i] != "E":
+                if rest.startswith("DF16b", i):
+                    args.append("__bf16"); i += 5
+                elif rest[i] == "f":
+                    args.append("float"); i += 1
+                elif rest.startswith("Lb", i):
+                    args.append("true" if rest[i + 2] == "1" else "false"); i += 4
+                elif rest.startswith("Li", i):
+                    j = rest.index("E", i)
+                    args.append(rest[i + 2:j]); i = j + 1
+                else:
+                    break
+        return "cp::%s%s" % (base, "<%s>" % ", ".join(args) if args else "")
+    name = name.replace("(anonymous namespace)::", "")
+    if name.startswith("void "):
+        name = name[5:]
+    cut = name.find("(")
+    return name if cut < 0 else name[:cut]
+
+
+def stats_main():
+    """Per (kernel, grid) durations from the kernel trace: the same kernel serves several
+    workloads of one bench run (the 128K and the 1M ring walk, ...), told apart by their grids."""
+    import json
+    trace_csv, bench_json, out, cmd = sys.argv[2:6]
+    line = json.loads(open(bench_json).read().strip().splitlines()[-1])
+    groups = collections.defaultdict(list)
+    for r in csv.DictReader(open(trace_csv)):
+        name = short_name(r["Kernel_Name"])
+        wg = [int(r["Workgroup_Size_" + a]) for a in "XYZ"]
+        grid = tuple(int(r["Grid_Size_" + a]) // w for a, w in zip("XYZ", wg))
+        groups[(name, grid)].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    total = sum(sum(v) for v in groups.values())
+    with open(out, "w") as f:
+        f.write("command:\n  %s\n\n" % cmd)
+        f.write("bench.py's own line of this run (HIP events around whole driver calls):\n")
+        f.write("  value %.2f %s   ms_per_step %.4f   steps %d   warmup %d\n"
+                % (line["value"], line["unit"], line["ms_per_step"], line["steps"], line["warmup"]))
+
+        def block(label, b):
+            if isinstance(b, dict) and "us_per_launch" in b:
+                f.write("  %-58s us_per_launch %10.2f  frac %.4f  %s\n"
+                        % (label, b["us_per_launch"], b.get("frac", float("nan")),
+                           b.get("kernel", "")[:60]))
+        block("roofline", line.get("roofline"))
+        for k, v in line.get("aux", {}).items():
+            if isinstance(v, dict):
+                block("aux.%s.roofline" % k, v.get("roofline"))
+            elif isinstance(v, list):
+                for e in v:
+                    if isinstance(e, dict):
+                        tag = e.get("workload", k)
+                        block("aux.%s[%s].roofline" % (k, tag), e.get("roofline"))
+                        block("aux.%s[%s].roofline_literal_step" % (k, tag),
+                              e.get("roofline_literal_step"))
+        f.write("\nper-kernel durations of the same process (rocprofv3 kernel trace), one row per "
+                "kernel and grid (workgroups x, y, z):\n")
+        f.write("%-64s %-16s %7s %14s %11s %11s %7s %11s %11s\n"
+                % ("kernel", "grid", "calls", "total_ns", "avg_ns", "median_ns", "pct", "min_ns",
+                   "max_ns"))
+        for (name, grid), d in sorted(groups.items(), key=lambda kv: -sum(kv[1])):
+            ours = "cp::" in name or "probe_kernel" in name
+            if not ours and sum(d) < 5e-4 * total:
+                continue
+            d.sort()
+            f.write("%-64s %-16s %7d %14d %11.0f %11d %7.3f %11d %11d\n"
+                    % (name[:64], "%dx%dx%d" % grid, len(d), sum(d), sum(d) / len(d),
+                       d[len(d) // 2], 100.0 * sum(d) / total, d[0], d[-1]))
+    print(out)
+
+
 def main():
     if len(sys.argv) > 1 and sys.argv[1] == "--mfma":
         return mfma_main()
+    if len(sys.argv) > 1 and sys.argv[1] == "--stats":
+        return stats_main()
     fetch_csv, write_csv, out_dir, workload, cmd = sys.argv[1:6]
     copy_bytes = 1 << 28
     rd = per_dispatch(fetch_csv, "FETCH_SIZE")
