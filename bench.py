@@ -246,7 +246,8 @@ def build_decode(w: W.Workload):
     return dict(ranks=ranks, q=q, q_pos=q_pos, bid=bid, lengths=lengths)
 
 
-def bench_decode(w: W.Workload, reps: int = 20, graph: bool = True, probe_only: bool = False):
+def bench_decode(w: W.Workload, reps: int = 20, graph: bool = True, probe_only: bool = False,
+                 cpu: bool = False):
     """Pass-Q decode (Algorithm 4) for 32 sequences x 1 token over 16 virtual ranks, queries
     gathered: every KV holder answers all 32 queries with one launch over its packed KV (the
     ranks' KV are distinct buffers, 1.4 GB in all, so nothing is reused from the 256 MB
@@ -340,6 +341,21 @@ def bench_decode(w: W.Workload, reps: int = 20, graph: bool = True, probe_only: 
         res[label] = {"us_per_call": round(us_c, 2),
                       "frac_hbm": round(call_bytes / us_c / 1e3 / PEAK_HBM_GBS, 4),
                       "launches": "decode kernel + its own merge over the splits"}
+    if cpu:
+        # the oracle on one holder's call (all 32 queries against rank 0's packed KV), in full
+        import oracle
+        r0 = st["ranks"][0]
+        q64, k64, v64 = W.to_f64(st["q"]), W.to_f64(r0["k"]), W.to_f64(r0["v"])
+        qp = st["q_pos"].cpu().numpy()
+        kp = r0["kv_pos"].cpu().numpy()
+        cu = r0["cu"].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.attn(q64, k64, v64, qp, kp, cu_q=np.arange(w.batch + 1, dtype=np.int32), cu_kv=cu)
+        dt = time.perf_counter() - t0
+        res["cpu_baseline"] = dict(
+            value=round(call_bytes / dt / 1e9, 4), unit="GB/s", cores=oracle.num_threads(),
+            kind="oracle", sample="one KV holder's whole call (32 queries x 16 heads against "
+                                  "its %d packed keys), %.2f s" % (r0["total"], dt))
     return res
 
 
@@ -804,7 +820,8 @@ def main():
     if not args.no_aux:
         if w.name == "prefill_128k":
             aux["prefill_1m"] = bench_prefill_1m_subset()
-        aux["decode"] = bench_decode(W.WORKLOADS["decode_b32"], reps=max(20, args.steps))
+        aux["decode"] = bench_decode(W.WORKLOADS["decode_b32"], reps=max(20, args.steps),
+                                     cpu=not args.no_cpu)
         torch.cuda.empty_cache()
         aux["hbm_read_probe"] = hbm_read_probe(
             int(aux["decode"]["kv_mb_per_rank"] * 1e6) // 4096 * 4096)

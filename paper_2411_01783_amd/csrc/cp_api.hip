@@ -456,12 +456,14 @@ int ring_prepare(const cp_ring_desc* d, bool decode, hipStream_t st, RingWork& w
   w.use_bounds = ring_uses_tile_bounds(d, decode);
   size_t off = 0;
   if (w.use_bounds) {
+    void* bounds[CP_MAX_PARTS];
     for (int b = 0; b < d->n_ranks; ++b) {
       w.bounds_off[b] = off;
-      if (launch_kv_tile_bounds(d->kv_pos[b], d->n_kv[b], (char*)d->workspace + off, st) != CP_OK)
-        return CP_ERR_LAUNCH;
+      bounds[b] = (char*)d->workspace + off;
       off += kv_tile_bounds_bytes(d->n_kv[b]);
     }
+    const int rc = launch_kv_tile_bounds_ring(d->n_ranks, d->kv_pos, d->n_kv, bounds, st);
+    if (rc != CP_OK) return rc;
   }
   w.call_ws = (char*)d->workspace + off;
   w.call_ws_bytes = d->workspace_bytes >= off ? d->workspace_bytes - off : 0;

@@ -49,6 +49,9 @@ size_t prefill_mfma_workspace_bytes(const cp_shape& s);
 size_t kv_tile_bounds_bytes(int64_t total_kv);
 int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_out,
                           hipStream_t stream);
+// Tile bounds of all shards of a ring in one launch; bounds_out[j] as for launch_kv_tile_bounds.
+int launch_kv_tile_bounds_ring(int n_shards, const int32_t* const* kv_pos, const int64_t* n_kv,
+                               void* const* bounds_out, hipStream_t stream);
 // `acc`, when not NULL, turns the launch into "merge into a running result": out / lse /
 // out_dtype are ignored, (acc->out, acc->lse) are read and updated (Equation 4), and if
 // acc->final_out is not NULL the merged O goes there in acc->final_dtype instead of back to

@@ -124,6 +124,42 @@ __global__ __launch_bounds__(256) void kv_tile_bounds_kernel(const int32_t* __re
   if (lane == 0) bounds[tile] = make_int2(lo, hi);
 }
 
+// The same for the shards of a whole ring in one launch (a launch per shard costs more than
+// the work: a shard of 8K keys is 64 tiles).
+struct BoundsTable {
+  const int32_t* kv_pos[CP_MAX_PARTS];
+  int2* bounds[CP_MAX_PARTS];
+  int32_t total_kv[CP_MAX_PARTS];
+  int32_t tile_begin[CP_MAX_PARTS + 1];  // first global tile index of every shard
+  int32_t n_shards;
+};
+__global__ __launch_bounds__(256) void kv_tile_bounds_ring_kernel(const BoundsTable t) {
+  const int gt = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (gt >= t.tile_begin[t.n_shards]) return;
+  int j = 0;
+  while (t.tile_begin[j + 1] <= gt) ++j;  // (wave-uniform; empty shards are skipped over)
+  const int tile = gt - t.tile_begin[j];
+  const int32_t* __restrict__ kv_pos = t.kv_pos[j];
+  const int32_t total_kv = t.total_kv[j];
+  const int lane = threadIdx.x & 63;
+  int lo = INT32_MAX, hi = INT32_MIN;
+#pragma unroll
+  for (int h = 0; h < TILE / 64; ++h) {
+    const int idx = tile * TILE + h * 64 + lane;
+    if (idx < total_kv) {
+      const int32_t x = kv_pos[idx];
+      lo = min(lo, x);
+      hi = max(hi, x);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    lo = min(lo, __shfl_xor(lo, o, 64));
+    hi = max(hi, __shfl_xor(hi, o, 64));
+  }
+  if (lane == 0) t.bounds[j][tile] = make_int2(lo, hi);
+}
+
 __device__ __forceinline__ floatx16_t mfma32(bf16x8_t a, bf16x8_t b, floatx16_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -206,6 +242,29 @@ int launch_kv_tile_bounds(const int32_t* kv_pos, int64_t total_kv, void* bounds_
   if (n_tiles == 0) return CP_OK;
   hipLaunchKernelGGL(kv_tile_bounds_kernel, dim3((n_tiles + 3) / 4), dim3(256), 0, stream, kv_pos,
                      (int32_t)total_kv, n_tiles, (int2*)bounds_out);
+  return check_launch();
+}
+
+int launch_kv_tile_bounds_ring(int n_shards, const int32_t* const* kv_pos, const int64_t* n_kv,
+                               void* const* bounds_out, hipStream_t stream) {
+  if (n_shards < 1 || n_shards > CP_MAX_PARTS) return CP_ERR_SHAPE;
+  BoundsTable t = {};
+  int64_t tiles = 0;
+  for (int j = 0; j < n_shards; ++j) {
+    if (n_kv[j] < 0 || n_kv[j] > INT32_MAX - TILE) return CP_ERR_SHAPE;
+    if (n_kv[j] > 0 && (kv_pos[j] == nullptr || bounds_out[j] == nullptr)) return CP_ERR_NULL;
+    t.kv_pos[j] = kv_pos[j];
+    t.bounds[j] = (int2*)bounds_out[j];
+    t.total_kv[j] = (int32_t)n_kv[j];
+    t.tile_begin[j] = (int32_t)tiles;
+    tiles += (n_kv[j] + TILE - 1) / TILE;
+    if (tiles > INT32_MAX - 4) return CP_ERR_SHAPE;
+  }
+  t.tile_begin[n_shards] = (int32_t)tiles;
+  t.n_shards = n_shards;
+  if (tiles == 0) return CP_OK;
+  hipLaunchKernelGGL(kv_tile_bounds_ring_kernel, dim3((unsigned)((tiles + 3) / 4)), dim3(256), 0,
+                     stream, t);
   return check_launch();
 }
 
