@@ -142,11 +142,14 @@ def stats_main():
     trace_csv, bench_json, out, cmd = sys.argv[2:6]
     line = json.loads(open(bench_json).read().strip().splitlines()[-1])
     groups = collections.defaultdict(list)
+    in_order = collections.defaultdict(list)   # (start, duration) per group, for the timed region
     for r in csv.DictReader(open(trace_csv)):
         name = short_name(r["Kernel_Name"])
         wg = [int(r["Workgroup_Size_" + a]) for a in "XYZ"]
         grid = tuple(int(r["Grid_Size_" + a]) // w for a, w in zip("XYZ", wg))
-        groups[(name, grid)].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+        dur = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+        groups[(name, grid)].append(dur)
+        in_order[(name, grid)].append((int(r["Start_Timestamp"]), dur))
     total = sum(sum(v) for v in groups.values())
     with open(out, "w") as f:
         f.write("command:\n  %s\n\n" % cmd)
@@ -170,6 +173,21 @@ def stats_main():
                         block("aux.%s[%s].roofline" % (k, tag), e.get("roofline"))
                         block("aux.%s[%s].roofline_literal_step" % (k, tag),
                               e.get("roofline_literal_step"))
+        # The headline's timed region: bench.py's first calls of the ring walk are the warm-up
+        # steps, then the timed steps, one launch per virtual rank each.
+        n_ranks = line.get("config", {}).get("virtual_ranks", 0)
+        head = [(k, v) for k, v in in_order.items() if "prefill_ring_walk_kernel" in k[0]]
+        if n_ranks and head:
+            key, seq = max(head, key=lambda kv: len(kv[1]))
+            seq.sort()
+            lo, hi = line["warmup"] * n_ranks, (line["warmup"] + line["steps"]) * n_ranks
+            timed = [d for _, d in seq[lo:hi]]
+            if len(timed) == hi - lo:
+                avg = sum(timed) / len(timed)
+                f.write("\ntimed region of the headline (launches %d..%d of %s in dispatch order): "
+                        "avg %.1f us, min %.1f, max %.1f; %d x avg = %.3f ms of ms_per_step %.3f\n"
+                        % (lo + 1, hi, key[0], avg / 1e3, min(timed) / 1e3, max(timed) / 1e3,
+                           n_ranks, n_ranks * avg / 1e6, line["ms_per_step"]))
         f.write("\nper-kernel durations of the same process (rocprofv3 kernel trace), one row per "
                 "kernel and grid (workgroups x, y, z):\n")
         f.write("%-64s %-16s %7s %14s %11s %11s %7s %11s %11s\n"
