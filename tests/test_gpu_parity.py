@@ -586,6 +586,17 @@ def test_decode_flat_ranges(oracle, lengths, bid):
     _decode_case(oracle, lengths, 16, 1, bid, 120 + len(lengths), unique_bid=True)
 
 
+def test_decode_flat_more_sequences_than_table_lanes(oracle):
+    """More than 64 sequences and queries: the entries of cu_seqlens_kv, bid and q_pos past the
+    per-lane tables come through scalar loads, the first sequence of a range by bisection."""
+    rng = np.random.default_rng(77)
+    lengths = [int(x) for x in rng.integers(0, 400, size=150)]
+    bid = [int(x) for x in rng.permutation(150)]
+    _decode_case(oracle, lengths, 16, 1, bid, 141, unique_bid=True)
+    # queries for the late sequences only: every lookup misses the 64-entry bid table first
+    _decode_case(oracle, lengths, 16, 1, list(range(149, 69, -1)), 142, unique_bid=True)
+
+
 def test_decode_flat_ranges_pads_and_groups(oracle):
     _decode_case(oracle, [500, 900, 64, 2000, 31], 16, 1, [3, 0, 1, 4], 131, pad_some=True,
                  unique_bid=True)
