@@ -692,7 +692,7 @@ def main():
     tflops = flop_step / sec / 1e12
 
     # dominant kernel: the ring walk, one launch per rank; HIP events around a whole driver call
-    # (16 launches and the 16 tile-bound pre-passes, 3.5 us each), once per timed step
+    # (16 launches and one tile-bound pre-pass over all shards), once per timed step
     walk_ms = event_times(lambda: B.cp_ring_passkv(ring), args.steps, 0)
     us_per_launch = float(np.median(walk_ms)) * 1e3 / w.n_ranks
     flop_per_launch = flop_step / w.n_ranks     # every rank sees the same number of pairs
