@@ -334,6 +334,31 @@ def test_ring_walk_in_one_launch_matches_unsharded(oracle, n, t, flags):
         B.cp_ring_passq(ring)
 
 
+@pytest.mark.parametrize("fused", [0, 1, 2])
+def test_ring_with_an_empty_and_uneven_kv_shards(oracle, fused):
+    """The KV of a ring need not be sharded like the queries (the mask is by position): one
+    rank holds no keys at all, another two ranks' worth, the third a ragged count. Covers the
+    one-launch tile-bound pre-pass over shards of different sizes, an empty one among them."""
+    n, t = 3, 6144 + 77
+    q, q64 = randn(61, (t, 16, 128))
+    k, k64 = randn(62, (t, 1, 128))
+    v, v64 = randn(63, (t, 1, 128))
+    pos = [B.cp_shard_positions(t, n, r) for r in range(n)]
+    kv = [np.concatenate([pos[0], pos[1][:-5]]), np.zeros(0, dtype=np.int32),
+          np.concatenate([pos[2], pos[1][-5:]])]
+    rows = np.r_[0:40, t // 2 - 8:t // 2 + 8, t - 40:t]
+    ref_o, ref_l = oracle.attn(q64[rows], k64, v64, rows, np.arange(t))
+    where = {int(p): (a, i) for a in range(n) for i, p in enumerate(pos[a])}
+    ring = B.Ring([dev(q[p]) for p in pos], [dev(k[p]) for p in kv], [dev(v[p]) for p in kv],
+                  [i32(p) for p in pos], [i32(p) for p in kv], out_dtype=torch.float32,
+                  fused_merge=fused)
+    out, lse = B.cp_ring_passkv(ring)
+    torch.cuda.synchronize()
+    got_o = torch.stack([out[where[int(r)][0]][where[int(r)][1]] for r in rows])
+    got_l = torch.stack([lse[where[int(r)][0]][where[int(r)][1]] for r in rows])
+    check(got_o, got_l, ref_o, ref_l, what="ring with an empty KV shard, fused_merge=%d" % fused)
+
+
 def test_ring_walk_gives_up_on_a_shard_that_never_arrives(oracle):
     """The host never sets one step's flag and allows three polls: every kernel still ends,
     the error word is set, and the ranks whose flags were all set are unaffected."""
