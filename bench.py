@@ -410,7 +410,7 @@ def bench_kv_append(reps: int = 20):
 # persistent-KV partial prefill, pass-Q (aux; launch-bound at small T)
 # ---------------------------------------------------------------------------
 
-def bench_partial_prefill(names, reps: int = 5):
+def bench_partial_prefill(names, reps: int = 5, cpu: bool = False):
     rows = []
     for name in names:
         w = W.WORKLOADS[name]
@@ -464,6 +464,18 @@ def bench_partial_prefill(names, reps: int = 5):
             flop / (n * n), row["passq_us_per_call"])
         row["passq_gathered_max_abs_diff"] = round(max(
             float((a.float() - b.float()).abs().max()) for a, b in zip(gring.out, ring.out)), 5)
+        if cpu and t_new <= 128:
+            # the oracle's own pass-Q ring (Algorithm 3: 16 x 16 partial attentions + 16 merges)
+            import oracle
+            q64 = [W.to_f64(x) for x in ring.tensors[0]]
+            k64 = [W.to_f64(x) for x in ring.tensors[1]]
+            v64 = [W.to_f64(x) for x in ring.tensors[2]]
+            t0 = time.perf_counter()
+            oracle.ring_passq(q64, k64, v64, qpos, kvpos)
+            dt = time.perf_counter() - t0
+            row["cpu_baseline"] = dict(value=round(flop / dt / 1e12, 5), unit="TFLOP/s",
+                                       cores=oracle.num_threads(), kind="oracle",
+                                       sample="the whole pass-Q ring of this workload, %.2f s" % dt)
         del gring
         rows.append(row)
         del ring, q, k, v
@@ -828,7 +840,7 @@ def main():
         torch.cuda.empty_cache()
         aux["partial_prefill"] = bench_partial_prefill(
             ["partial_prefill_128k_t128", "partial_prefill_128k_t1024",
-             "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"])
+             "partial_prefill_128k_t2048", "partial_prefill_128k_t8192"], cpu=not args.no_cpu)
         aux["paper_step_shapes"] = bench_paper_step_shapes()
         aux["kv_append"] = bench_kv_append()
         aux["selector"] = selector_table(tflops * 1e12)
