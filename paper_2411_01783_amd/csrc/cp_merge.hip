@@ -207,12 +207,27 @@ int launch_merge(int64_t rows, int32_t head_dim, int32_t n_parts, const void* co
   return launch_np<bf16_t, bf16_t, 8>(ptrs, n_parts, rows, head_dim, out, lse_out, stream);
 }
 
+constexpr int64_t kStridedStreamRows = 4096;
+
 int launch_merge_strided(int64_t rows, int32_t head_dim, int32_t n_parts, const float* parts_out,
                          const float* parts_lse, int64_t part_stride_rows, void* out,
                          int32_t out_dtype, float* lse_out, hipStream_t stream) {
   const int64_t n_vec = rows * (head_dim / 4);
   if (n_vec == 0) return CP_OK;
   if (n_parts < 1 || n_parts > CP_MAX_PARTS || n_vec > 0x7fffffffLL * 64) return CP_ERR_SHAPE;
+  // Many rows: the work is bound by bandwidth, not by latency, and the streaming kernel with
+  // its compile-time part counts moves it faster (measured at 16384 rows x 4 parts: 14 us
+  // here against 8 us there; with a run-time part count it is slower than this kernel).
+  if (rows >= kStridedStreamRows && (n_parts == 2 || n_parts == 4 || n_parts == 8 || n_parts == 16)) {
+    const void* outs[CP_MAX_PARTS];
+    const float* lses[CP_MAX_PARTS];
+    for (int s = 0; s < n_parts; ++s) {
+      outs[s] = parts_out + (int64_t)s * part_stride_rows * head_dim;
+      lses[s] = parts_lse + (int64_t)s * part_stride_rows;
+    }
+    return launch_merge(rows, head_dim, n_parts, outs, lses, CP_FP32, out, out_dtype, lse_out,
+                        stream);
+  }
   const dim3 grid((unsigned)((n_vec + 63) / 64));
   if (out_dtype == CP_FP32)
     hipLaunchKernelGGL(merge_split_kernel<float>, grid, dim3(64), 0, stream, parts_out, parts_lse,
