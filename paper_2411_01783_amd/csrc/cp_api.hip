@@ -176,7 +176,7 @@ int cp_attn_partial_accumulate(const cp_shape* shape, const void* q, const void*
   const cp_shape& s = *shape;
   if (final_out != nullptr && final_dtype != CP_BF16 && final_dtype != CP_FP32)
     return CP_ERR_UNSUPPORTED;
-  if (s.batch != 1 || !mfma_prefill_applies(s) || prefill_mfma_splits_kv(s))
+  if (s.batch != 1 || !mfma_prefill_applies(s) || prefill_mfma_splits_kv(s, true))
     return CP_ERR_UNSUPPORTED;
   if (s.total_q > 0 && (q == nullptr || q_pos == nullptr || acc_out == nullptr || acc_lse == nullptr))
     return CP_ERR_NULL;
@@ -473,7 +473,8 @@ int ring_prepare(const cp_ring_desc* d, bool decode, hipStream_t st, RingWork& w
   if (!decode && w.use_bounds && (d->aux_stream != nullptr || d->fused_merge)) {
     for (int a = 0; a < d->n_ranks && !scratch; ++a)
       for (int b = 0; b < d->n_ranks && !scratch; ++b)
-        scratch = d->n_q[a] > 0 && prefill_mfma_splits_kv(ring_shape(d, a, b, false));
+        scratch = d->n_q[a] > 0 &&
+                  prefill_mfma_splits_kv(ring_shape(d, a, b, false), d->fused_merge != 0);
   }
   if (d->fused_merge && d->n_ranks > 1 && scratch) return CP_ERR_UNSUPPORTED;
   if (d->aux_stream != nullptr && !decode && w.use_bounds && !d->fused_merge) {

@@ -63,7 +63,8 @@ struct PrefillAccumulate {
   float* final_lse;  // or NULL
   int32_t final_dtype;
 };
-bool prefill_mfma_splits_kv(const cp_shape& s);
+// `merging`: for a call that merges into a running result in its epilogue (see make_plan).
+bool prefill_mfma_splits_kv(const cp_shape& s, bool merging);
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,

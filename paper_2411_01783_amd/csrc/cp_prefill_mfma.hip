@@ -186,17 +186,20 @@ struct Plan {
 
 inline size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-Plan make_plan(const cp_shape& s) {
+// `merging`: the call merges into a running result in its epilogue, which only unsplit
+// launches do; then (and for the ring walk) the KV axis is left whole from 128 workgroups on.
+Plan make_plan(const cp_shape& s, bool merging = false) {
   Plan pl;
   const int group = s.n_q_heads / s.n_kv_heads;
   const int64_t rows = s.total_q * group;
   pl.n_tiles = (int)((s.total_kv + TILE - 1) / TILE);
   pl.n_row_blocks = (int)((rows + BM - 1) / BM);
-  // Split the KV axis when the row blocks alone cannot occupy the 256 CUs. Every split
+  // Split the KV axis when the row blocks alone cannot occupy the 256 CUs (the cost model
+  // below keeps 129 .. 255 workgroups whole: two splits would need a second round). Every split
   // costs one fp32 partial of the output, so keep at least kMinTilesPerSplit tiles per split.
   const int64_t wgs = (int64_t)pl.n_row_blocks * s.n_kv_heads;
   int splits = 1;
-  if (wgs > 0 && wgs < 128 && pl.n_tiles >= 2 * kMinTilesPerSplit) {
+  if (wgs > 0 && wgs < (merging ? 128 : 256) && pl.n_tiles >= 2 * kMinTilesPerSplit) {
     // Cost of a split count, in units of one tile step of a workgroup: the workgroups run in
     // rounds of 256 (one per CU), each round walks its tiles plus about three tile steps of
     // start-up and epilogue, and every split adds one fp32 partial to write and to merge.
@@ -268,14 +271,16 @@ int launch_kv_tile_bounds_ring(int n_shards, const int32_t* const* kv_pos, const
   return check_launch();
 }
 
-bool prefill_mfma_splits_kv(const cp_shape& s) { return make_plan(s).n_splits > 1; }
+bool prefill_mfma_splits_kv(const cp_shape& s, bool merging) {
+  return make_plan(s, merging).n_splits > 1;
+}
 
 int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const void* k,
                         const void* v, const int32_t* q_pos, const int32_t* kv_pos, void* out,
                         float* lse, int32_t out_dtype, void* workspace, size_t workspace_bytes,
                         const void* tile_bounds, const int32_t* q_lo, hipStream_t stream,
                         const PrefillAccumulate* acc) {
-  const Plan pl = make_plan(s);
+  const Plan pl = make_plan(s, acc != nullptr);
   if (acc != nullptr && (pl.n_splits > 1 || q_lo != nullptr)) return CP_ERR_UNSUPPORTED;
   if (workspace_bytes < pl.bounds_bytes + pl.part_out_bytes + pl.part_lse_bytes)
     return CP_ERR_WORKSPACE;
@@ -338,7 +343,7 @@ int launch_prefill_mfma(const cp_shape& s, float scale, const void* q, const voi
 
 bool prefill_ring_walk_applies(const cp_shape& s, int n_shards) {
   if (n_shards < 1 || n_shards > kMaxRingShards) return false;
-  const Plan pl = make_plan(s);
+  const Plan pl = make_plan(s, true);
   return pl.n_row_blocks > 0 && pl.n_splits == 1;
 }
 
@@ -352,7 +357,7 @@ int launch_prefill_mfma_ring(const cp_shape& s, float scale, const void* q, cons
   if (arrived != nullptr && (error == nullptr || spin_limit < 1)) return CP_ERR_SHAPE;
   if (s.n_kv_heads > 65535) return CP_ERR_SHAPE;
   if (s.total_q * (s.n_q_heads / s.n_kv_heads) > 0x7fffffffLL) return CP_ERR_SHAPE;  // 31-bit rows
-  const Plan pl = make_plan(s);
+  const Plan pl = make_plan(s, true);
   Params p = {};
   p.q = (const bf16_t*)q; p.q_pos = q_pos;
   p.k = (const bf16_t*)k[0]; p.v = (const bf16_t*)v[0]; p.kv_pos = kv_pos[0];
