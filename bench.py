@@ -292,6 +292,13 @@ def bench_decode(w: W.Workload, reps: int = 20, graph: bool = True, probe_only: 
         "hbm", "decode_flat_kernel (+ 1/16 of the ring's decode_flat_merge_kernel)",
         ring_bytes / n, us_rank,
         None if t_kernel is None or t_merge is None else t_kernel + t_merge / n)
+    k_us = stored_kernel_us("cp::decode_flat_kernel", "512x1x1")
+    if k_us is not None:
+        res["kernel_alone"] = {
+            "kernel": "decode_flat_kernel", "us_per_launch": round(k_us, 2),
+            "frac_hbm": round(ring_bytes / n / k_us / 1e3 / PEAK_HBM_GBS, 4),
+            "source": "profiles/bench_default_run_kernel_stats.txt (rocprofv3 kernel trace of "
+                      "the default run, stored in the repository; not measured in this run)"}
     ref = gring.out_all.clone()
     if graph:
         # the same ring replayed from one HIP graph (the paper runs decode under graphs,
@@ -601,6 +608,19 @@ def pmc_probe(st):
     torch.cuda.synchronize()
     bench_decode(W.WORKLOADS["decode_b32"], probe_only=True)
     print("pmc probe done")
+
+
+def stored_kernel_us(kernel: str, grid: str):
+    """Average duration (us) of a kernel and grid in the committed kernel-trace summary of the
+    default bench run, or None."""
+    path = os.path.join(ROOT, "profiles", "bench_default_run_kernel_stats.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 5 and f[0] == kernel and f[1] == grid:
+            return float(f[4]) / 1e3
+    return None
 
 
 def stored_traffic(kernel: str, workload: str):
